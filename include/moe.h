@@ -1,0 +1,179 @@
+/*
+ * moe.h -- C ABI of the MI355X (gfx950) MoE expert-module library.
+ *
+ * The library computes the sparse MoE layer of the paper's Sec. 2 ("MoE inference": a router
+ * assigns each token to top-k experts, each token is processed by its k experts, the output
+ * is the weighted sum of their outputs, optionally plus shared experts every token passes
+ * through) on ONE large accumulated token batch, which is what module-based batching
+ * (Sec. 4.2) hands to the expert module.  Experts are SwiGLU MLPs:
+ *     expert_e(x) = ( silu(x W1_e) * (x W3_e) ) W2_e ,   silu(z) = z / (1 + exp(-z)).
+ *
+ * Conventions for every entry point
+ *  - Plain C types only.  "device" pointers are HIP device memory on the context's GPU;
+ *    "host" pointers are ordinary process memory.  bf16 data is passed as `void*`.
+ *  - All matrices are dense, row-major, without padding.
+ *  - Ownership: the caller owns every buffer, including the workspace.  The library
+ *    allocates device memory only inside moe_create (small tables) and frees it in
+ *    moe_destroy.  Nothing is retained from the caller's buffers after a call's kernels
+ *    have run.
+ *  - Asynchrony: a call validates its arguments, enqueues kernels on `hip_stream`
+ *    (a hipStream_t, NULL = the default stream) and returns without synchronising.
+ *    One context must be used from one host thread and one stream at a time.
+ *  - Errors: every call returns a moe_status; nothing has been enqueued when the status is
+ *    MOE_E_ARG / MOE_E_UNSUPPORTED / MOE_E_WORKSPACE.  moe_last_error gives the message.
+ *  - Expert weight tables are HOST arrays of DEVICE pointers, read when the call is made,
+ *    so that a weight streamer may repoint them between calls (sequential execution of
+ *    experts with prefetched weights, Sec. 4.2).
+ *  - Weight layout on the hot path is the PACKED one: every matrix is stored with the
+ *    contraction dimension contiguous, i.e. W1p_e, W3p_e are [F,H] and W2p_e is [H,F]
+ *    (the transposes of the logical [H,F] / [F,H] matrices).  moe_pack_weight converts a
+ *    logical matrix once; weights are static, so this is not part of the timed path.
+ *  - Limits: H % 64 == 0, F % 64 == 0, 1 <= top_k <= E <= 256, top_k <= 64,
+ *    0 <= num_shared <= 8, every matrix below 4 GiB.  Other shapes: MOE_E_UNSUPPORTED.
+ */
+#ifndef MOE_MI355_H
+#define MOE_MI355_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct moe_ctx moe_ctx; /* opaque: device id, pointer-table slots, profiling events, error text */
+
+typedef enum {
+    MOE_OK = 0,
+    MOE_E_ARG = 1,         /* null pointer, non-positive size, top_k > E, ... */
+    MOE_E_UNSUPPORTED = 2, /* a shape outside the limits above */
+    MOE_E_WORKSPACE = 3,   /* workspace_bytes smaller than moe_workspace_bytes(shape) */
+    MOE_E_HIP = 4          /* a HIP runtime call or kernel launch failed */
+} moe_status;
+
+typedef struct {
+    int32_t T;           /* tokens in the accumulated batch */
+    int32_t H;           /* hidden size */
+    int32_t F;           /* expert FFN width */
+    int32_t E;           /* routed experts */
+    int32_t top_k;       /* experts per token */
+    int32_t num_shared;  /* always-on shared experts, each of width F */
+    int32_t renormalize; /* 1: weights divided by their sum over the selected k; 0: raw softmax probabilities */
+    float routed_scale;  /* multiplies the routed weights (1.0 in all reference workloads) */
+} moe_shape;
+
+/* Stage ids for the profiling interface. */
+enum {
+    MOE_STAGE_ROUTE = 0,
+    MOE_STAGE_PERMUTE_INDEX = 1, /* histogram + scan + stable placement */
+    MOE_STAGE_PERMUTE_GATHER = 2,
+    MOE_STAGE_PLAN = 3,          /* tile work-list from expert_offsets */
+    MOE_STAGE_FFN_GATE_UP = 4,   /* grouped GEMM 1 + SiLU-gate epilogue */
+    MOE_STAGE_FFN_DOWN = 5,      /* grouped GEMM 2 */
+    MOE_STAGE_COMBINE = 6,
+    MOE_STAGE_COUNT = 7
+};
+
+/* Creates a context bound to HIP device `device` (host call; allocates the small device
+ * tables).  *out is NULL on failure. */
+moe_status moe_create(moe_ctx** out, int device);
+void moe_destroy(moe_ctx* ctx);
+/* Message of the last failing call on this context ("" if none); valid until the next call. */
+const char* moe_last_error(const moe_ctx* ctx);
+
+/* Bytes of device workspace that is enough for any call below with this shape, for ANY
+ * routing outcome (per-expert token counts are unknown until run time, Sec. 4.3).
+ * Returns 0 for an invalid shape. */
+size_t moe_workspace_bytes(const moe_shape* shape);
+
+/* Tuning knobs (host call).  Unknown key or out-of-range value: MOE_E_ARG.
+ *   "gemm_wave_rows"  1 | 2   wave grid of the GEMM workgroup is (rows x 4/rows)
+ *   "gemm_group_m"    1..64   m-tiles swept together along n (L2 reuse of weight panels)
+ *   "xcd_remap"       0 | 1   give each XCD runs of consecutive tiles
+ *   "small_tiles"     0 | 1   use 128/64/32-row tiles for the ragged tail of an expert */
+moe_status moe_set_option(moe_ctx* ctx, const char* key, int32_t value);
+
+/* One-time weight packing: w_logical [rows, cols] bf16 (device) -> w_packed [cols, rows]
+ * bf16 (device, distinct buffer).  rows, cols multiples of 8. */
+moe_status moe_pack_weight(moe_ctx* ctx, const void* w_logical, int32_t rows, int32_t cols,
+                           void* w_packed, void* hip_stream);
+
+/* Router (Sec. 2: "a router assigns each token to a subset of experts, typically using a
+ * top-k selection strategy").  logit[t,e] = sum_h x[t,h] Wg[h,e] (+ gate_bias[e]) in fp32;
+ * p = softmax over all E; the k largest logits are selected (ties: lower expert id),
+ * listed in descending order; weight = p (divided by the sum over the selected k when
+ * renormalize) * routed_scale.
+ *   x_bf16 [T,H] device, wg_bf16 [H,E] device (logical layout), gate_bias [E] fp32 device or NULL
+ *   topk_idx [T,k] int32 device out, topk_w [T,k] fp32 device out,
+ *   logits_or_null [T,E] fp32 device out (for near-tie reports) or NULL. */
+moe_status moe_route(moe_ctx* ctx, const moe_shape* shape, const void* x_bf16, const void* wg_bf16,
+                     const float* gate_bias, int32_t* topk_idx, float* topk_w, float* logits_or_null,
+                     void* hip_stream);
+
+/* Groups the T*k (token, rank) pairs by expert ("tokens routed to an expert", Table 1; the
+ * counts are only known at run time, Sec. 4.3).  Order: ascending expert, then ascending
+ * token.  expert_offsets[e] = first row of expert e (expert_offsets[E] = T*k);
+ * perm[r] = t*k+j of the pair at row r; inv_perm[t*k+j] = r; x_perm[r,:] = x[t,:].
+ *   topk_idx [T,k] int32 device in (every id in [0,E); not validated)
+ *   x_perm_bf16 [T*k,H] device out, or NULL to skip the row gather
+ *   expert_offsets [E+1], perm [T*k], inv_perm [T*k] int32 device out
+ *   row_token_or_null [T*k] int32 device out: row_token[r] = perm[r] / k, or NULL
+ *   workspace: device, at least moe_workspace_bytes(shape). */
+moe_status moe_permute(moe_ctx* ctx, const moe_shape* shape, const void* x_bf16, const int32_t* topk_idx,
+                       void* x_perm_bf16, int32_t* expert_offsets, int32_t* perm, int32_t* inv_perm,
+                       int32_t* row_token_or_null, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Per-expert SwiGLU FFN over the grouped rows (Sec. 2 "each token is processed by k selected
+ * experts"; experts with no rows are skipped), as two grouped bf16 GEMMs with fp32
+ * accumulation: h = silu(X_e W1_e) * (X_e W3_e) rounded to bf16, then y = h W2_e rounded
+ * to bf16.  Shared experts E..E+num_shared-1 run on all T tokens of x; their outputs are
+ * summed (one GEMM over the concatenated contraction dimension) into y_shared.
+ *   x_perm_bf16 [T*k,H] device in; ignored (may be NULL) when row_token is given
+ *   row_token_or_null [T*k] int32 device: row r of the expert input is x[row_token[r],:]
+ *   x_bf16 [T,H] device in: needed when num_shared > 0 or row_token is given, else may be NULL
+ *   expert_offsets [E+1] int32 device in
+ *   w1p, w3p, w2p: host arrays of E+num_shared device pointers, packed layout (see above)
+ *   h_scratch_bf16 [(T*k + T*num_shared), F] device scratch
+ *   y_perm_bf16 [T*k,H] device out; y_shared_bf16 [T,H] device out (NULL iff num_shared == 0)
+ *   workspace: device, at least moe_workspace_bytes(shape). */
+moe_status moe_grouped_ffn(moe_ctx* ctx, const moe_shape* shape, const void* x_perm_bf16,
+                           const int32_t* row_token_or_null, const void* x_bf16,
+                           const int32_t* expert_offsets, const void* const* w1p, const void* const* w3p,
+                           const void* const* w2p, void* h_scratch_bf16, void* y_perm_bf16,
+                           void* y_shared_bf16, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Weighted sum back in token order (Sec. 2 "weighted average of the outputs from these
+ * experts", plus the shared expert all tokens pass through):
+ *   out[t,:] = sum_{j<k} topk_w[t,j] * y_perm[inv_perm[t*k+j],:] (+ y_shared[t,:]),
+ * fp32 accumulation in the order j = 0..k-1 then shared, one store per element, no atomics.
+ *   y_perm_bf16 [T*k,H], inv_perm [T*k], topk_w [T,k] fp32 (already carries routed_scale),
+ *   y_shared_or_null [T,H] bf16, out_bf16 [T,H]: all device. */
+moe_status moe_combine(moe_ctx* ctx, const moe_shape* shape, const void* y_perm_bf16, const int32_t* inv_perm,
+                       const float* topk_w, const void* y_shared_or_null, void* out_bf16, void* hip_stream);
+
+/* The whole expert module on one stream: route -> permute (indices only; the row gather is
+ * fused into the first GEMM's loads) -> grouped FFN -> combine.  Same results as the staged
+ * calls bit for bit.  All intermediates live in `workspace`. */
+moe_status moe_layer(moe_ctx* ctx, const moe_shape* shape, const void* x_bf16, const void* wg_bf16,
+                     const float* gate_bias, const void* const* w1p, const void* const* w3p,
+                     const void* const* w2p, void* out_bf16, void* workspace, size_t workspace_bytes,
+                     void* hip_stream);
+
+/* Device pointers into a workspace last used by moe_layer with this shape, for inspection:
+ * topk_idx [T,k] int32, topk_w [T,k] fp32, expert_offsets [E+1] int32, inv_perm [T*k] int32.
+ * Any out-pointer may be NULL. */
+moe_status moe_layer_views(const moe_shape* shape, void* workspace, int32_t** topk_idx, float** topk_w,
+                           int32_t** expert_offsets, int32_t** inv_perm);
+
+/* Profiling.  While enabled, every kernel group a call enqueues is bracketed by HIP events on
+ * the call's stream.  moe_profile_read waits for the recorded events, adds the elapsed
+ * milliseconds per stage into ms_sum[MOE_STAGE_COUNT] and the number of intervals into
+ * launches[MOE_STAGE_COUNT], and clears the record.  At most 8192 intervals are kept
+ * between reads (further ones are dropped). */
+moe_status moe_profile_enable(moe_ctx* ctx, int32_t on);
+moe_status moe_profile_read(moe_ctx* ctx, double* ms_sum, int32_t* launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_MI355_H */

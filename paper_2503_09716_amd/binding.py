@@ -1,0 +1,213 @@
+"""Thin ctypes binding of libmoe_mi355.so (the C ABI declared in include/moe.h).
+
+Argument marshalling only: torch supplies device memory and the current stream; every step
+of the MoE expert module runs in the library's HIP kernels.  There is no fallback: if the
+library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libmoe_mi355.so")
+
+STAGES = ["route", "permute_index", "permute_gather", "plan", "ffn_gate_up", "ffn_down", "combine"]
+
+EXPORTS = [
+    "moe_create", "moe_destroy", "moe_last_error", "moe_workspace_bytes", "moe_set_option", "moe_pack_weight",
+    "moe_route", "moe_permute", "moe_grouped_ffn", "moe_combine", "moe_layer", "moe_layer_views",
+    "moe_profile_enable", "moe_profile_read",
+]
+
+
+class MoeShape(C.Structure):
+    _fields_ = [("T", C.c_int32), ("H", C.c_int32), ("F", C.c_int32), ("E", C.c_int32), ("top_k", C.c_int32),
+                ("num_shared", C.c_int32), ("renormalize", C.c_int32), ("routed_scale", C.c_float)]
+
+
+class MoeError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__("moe status %d: %s" % (status, msg))
+        self.status = status
+
+
+_lib = None
+
+
+def load_library():
+    """Loads the in-tree library (building it first only if it does not exist yet)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from .build import build
+        build()
+    lib = C.CDLL(LIB_PATH)
+    vp, i32p, f32p = C.c_void_p, C.c_void_p, C.c_void_p
+    sp = C.POINTER(MoeShape)
+    tab = C.POINTER(C.c_void_p)
+    lib.moe_create.argtypes = [C.POINTER(C.c_void_p), C.c_int]
+    lib.moe_destroy.argtypes = [C.c_void_p]
+    lib.moe_destroy.restype = None
+    lib.moe_last_error.argtypes = [C.c_void_p]
+    lib.moe_last_error.restype = C.c_char_p
+    lib.moe_workspace_bytes.argtypes = [sp]
+    lib.moe_workspace_bytes.restype = C.c_size_t
+    lib.moe_set_option.argtypes = [C.c_void_p, C.c_char_p, C.c_int32]
+    lib.moe_pack_weight.argtypes = [C.c_void_p, vp, C.c_int32, C.c_int32, vp, vp]
+    lib.moe_route.argtypes = [C.c_void_p, sp, vp, vp, f32p, i32p, f32p, f32p, vp]
+    lib.moe_permute.argtypes = [C.c_void_p, sp, vp, i32p, vp, i32p, i32p, i32p, i32p, vp, C.c_size_t, vp]
+    lib.moe_grouped_ffn.argtypes = [C.c_void_p, sp, vp, i32p, vp, i32p, tab, tab, tab, vp, vp, vp, vp, C.c_size_t, vp]
+    lib.moe_combine.argtypes = [C.c_void_p, sp, vp, i32p, f32p, vp, vp, vp]
+    lib.moe_layer.argtypes = [C.c_void_p, sp, vp, vp, f32p, tab, tab, tab, vp, vp, C.c_size_t, vp]
+    lib.moe_layer_views.argtypes = [sp, vp, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
+                                    C.POINTER(C.c_void_p)]
+    lib.moe_profile_enable.argtypes = [C.c_void_p, C.c_int32]
+    lib.moe_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
+    for name in EXPORTS:
+        if name not in ("moe_destroy", "moe_last_error", "moe_workspace_bytes"):
+            getattr(lib, name).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def make_shape(T, H, F, E, top_k, num_shared=0, renormalize=True, routed_scale=1.0) -> MoeShape:
+    return MoeShape(int(T), int(H), int(F), int(E), int(top_k), int(num_shared), 1 if renormalize else 0,
+                    float(routed_scale))
+
+
+def shape_of(cfg) -> MoeShape:
+    return make_shape(cfg.T, cfg.H, cfg.F, cfg.E, cfg.top_k, cfg.num_shared, cfg.renormalize, cfg.routed_scale)
+
+
+def workspace_bytes(shape: MoeShape) -> int:
+    return int(load_library().moe_workspace_bytes(C.byref(shape)))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensor required"
+    return C.c_void_p(t.data_ptr())
+
+
+def _table(ws: Sequence[torch.Tensor]):
+    for w in ws:
+        assert w.is_cuda and w.is_contiguous()
+    return (C.c_void_p * len(ws))(*[w.data_ptr() for w in ws])
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+class Moe:
+    """One library context on one GPU.  Methods mirror the C entry points one to one."""
+
+    def __init__(self, device: int = 0):
+        self.lib = load_library()
+        self.device = device
+        h = C.c_void_p()
+        st = self.lib.moe_create(C.byref(h), device)
+        if st != 0 or not h:
+            raise MoeError(st, "moe_create failed on device %d" % device)
+        self.h = h
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.moe_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, st: int):
+        if st != 0:
+            raise MoeError(st, self.lib.moe_last_error(self.h).decode())
+
+    def set_option(self, key: str, value: int):
+        self._check(self.lib.moe_set_option(self.h, key.encode(), int(value)))
+
+    def new_workspace(self, shape: MoeShape) -> torch.Tensor:
+        n = workspace_bytes(shape)
+        if n == 0:
+            raise MoeError(2, "unsupported or invalid shape")
+        return torch.empty(n, dtype=torch.uint8, device="cuda:%d" % self.device)
+
+    # ---- one-time weight packing -------------------------------------------------------
+    def pack_weight(self, w: torch.Tensor) -> torch.Tensor:
+        rows, cols = w.shape
+        out = torch.empty((cols, rows), dtype=torch.bfloat16, device=w.device)
+        self._check(self.lib.moe_pack_weight(self.h, _ptr(w), rows, cols, _ptr(out), _stream()))
+        return out
+
+    def pack_experts(self, w1: Sequence[torch.Tensor], w3: Sequence[torch.Tensor], w2: Sequence[torch.Tensor]):
+        return ([self.pack_weight(w) for w in w1], [self.pack_weight(w) for w in w3],
+                [self.pack_weight(w) for w in w2])
+
+    # ---- staged calls ------------------------------------------------------------------
+    def route(self, shape, x, wg, bias, topk_idx, topk_w, logits=None):
+        self._check(self.lib.moe_route(self.h, C.byref(shape), _ptr(x), _ptr(wg), _ptr(bias), _ptr(topk_idx),
+                                       _ptr(topk_w), _ptr(logits), _stream()))
+
+    def permute(self, shape, x, topk_idx, x_perm, expert_offsets, perm, inv_perm, row_token, workspace):
+        self._check(self.lib.moe_permute(self.h, C.byref(shape), _ptr(x), _ptr(topk_idx), _ptr(x_perm),
+                                         _ptr(expert_offsets), _ptr(perm), _ptr(inv_perm), _ptr(row_token),
+                                         _ptr(workspace), workspace.numel(), _stream()))
+
+    def grouped_ffn(self, shape, x_perm, row_token, x, expert_offsets, w1p, w3p, w2p, h_scratch, y_perm, y_shared,
+                    workspace):
+        self._check(self.lib.moe_grouped_ffn(self.h, C.byref(shape), _ptr(x_perm), _ptr(row_token), _ptr(x),
+                                             _ptr(expert_offsets), _table(w1p), _table(w3p), _table(w2p),
+                                             _ptr(h_scratch), _ptr(y_perm), _ptr(y_shared), _ptr(workspace),
+                                             workspace.numel(), _stream()))
+
+    def combine(self, shape, y_perm, inv_perm, topk_w, y_shared, out):
+        self._check(self.lib.moe_combine(self.h, C.byref(shape), _ptr(y_perm), _ptr(inv_perm), _ptr(topk_w),
+                                         _ptr(y_shared), _ptr(out), _stream()))
+
+    # ---- fused call --------------------------------------------------------------------
+    def layer(self, shape, x, wg, bias, w1p, w3p, w2p, out, workspace, tables=None):
+        t1, t3, t2 = tables if tables is not None else (_table(w1p), _table(w3p), _table(w2p))
+        self._check(self.lib.moe_layer(self.h, C.byref(shape), _ptr(x), _ptr(wg), _ptr(bias), t1, t3, t2,
+                                       _ptr(out), _ptr(workspace), workspace.numel(), _stream()))
+
+    def tables(self, w1p, w3p, w2p):
+        """Pre-marshalled pointer tables, so a timed loop does not rebuild them per call."""
+        return _table(w1p), _table(w3p), _table(w2p)
+
+    def layer_views(self, shape, workspace):
+        """Routing results of the last layer() call, as torch views into the workspace."""
+        p = [C.c_void_p() for _ in range(4)]
+        st = self.lib.moe_layer_views(C.byref(shape), _ptr(workspace), *[C.byref(q) for q in p])
+        if st != 0:
+            raise MoeError(st, "moe_layer_views")
+        base = workspace.data_ptr()
+        R = shape.T * shape.top_k
+
+        def view(ptr, nbytes, dtype, shp):
+            off = ptr.value - base
+            return workspace[off:off + nbytes].view(dtype).view(*shp)
+        return {
+            "topk_idx": view(p[0], R * 4, torch.int32, (shape.T, shape.top_k)),
+            "topk_w": view(p[1], R * 4, torch.float32, (shape.T, shape.top_k)),
+            "expert_offsets": view(p[2], (shape.E + 1) * 4, torch.int32, (shape.E + 1,)),
+            "inv_perm": view(p[3], R * 4, torch.int32, (R,)),
+        }
+
+    # ---- profiling ---------------------------------------------------------------------
+    def profile_enable(self, on: bool):
+        self._check(self.lib.moe_profile_enable(self.h, 1 if on else 0))
+
+    def profile_read(self):
+        ms = (C.c_double * len(STAGES))()
+        n = (C.c_int32 * len(STAGES))()
+        self._check(self.lib.moe_profile_read(self.h, ms, n))
+        return {s: (ms[i], n[i]) for i, s in enumerate(STAGES)}

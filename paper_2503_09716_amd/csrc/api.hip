@@ -1,0 +1,433 @@
+// C-ABI layer: argument validation, workspace carving, weight pointer tables, profiling events.
+// Every step of the path runs in the kernels of this library; this file only enqueues them.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <vector>
+
+#include "common.h"
+
+using namespace moe;
+
+namespace {
+
+constexpr int TABLE_SLOTS = 8;
+constexpr int MAX_GROUPS = 256;
+constexpr int PROF_MAX = 8192;
+
+struct ProfRec {
+    int stage;
+    hipEvent_t a, b;
+};
+
+}  // namespace
+
+struct moe_ctx {
+    int device = 0;
+    char err[512] = {0};
+    GemmConfig gemm{2, 8, 1, 1};
+    // Ring of device pointer tables [3][MAX_GROUPS] (W1p, W3p, W2p), each with a pinned host
+    // staging copy and an event marking the end of its upload.
+    void** d_tab[TABLE_SLOTS] = {nullptr};
+    void** h_tab[TABLE_SLOTS] = {nullptr};
+    hipEvent_t tab_done[TABLE_SLOTS] = {nullptr};
+    int tab_next = 0;
+    int tab_cur = -1;
+    int tab_n = 0;
+    std::vector<const void*> tab_shadow;  // contents of slot tab_cur
+    // profiling
+    bool prof = false;
+    std::vector<ProfRec> recs;
+    std::vector<hipEvent_t> pool;
+};
+
+namespace {
+
+moe_status fail(moe_ctx* c, moe_status st, const char* fmt, ...) {
+    if (c) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(c->err, sizeof(c->err), fmt, ap);
+        va_end(ap);
+    }
+    return st;
+}
+
+#define HIP_TRY(ctx, expr)                                                                      \
+    do {                                                                                        \
+        hipError_t e_ = (expr);                                                                 \
+        if (e_ != hipSuccess) return fail(ctx, MOE_E_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+const char* shape_problem(const moe_shape* s, moe_status* st) {
+    *st = MOE_E_ARG;
+    if (!s) return "shape is NULL";
+    if (s->T < 1 || s->H < 1 || s->F < 1 || s->E < 1 || s->top_k < 1) return "T, H, F, E, top_k must be >= 1";
+    if (s->top_k > s->E) return "top_k > E";
+    if (s->num_shared < 0) return "num_shared < 0";
+    if (s->renormalize != 0 && s->renormalize != 1) return "renormalize must be 0 or 1";
+    *st = MOE_E_UNSUPPORTED;
+    if (s->H % 64 || s->F % 64) return "H and F must be multiples of 64";
+    if (s->E > 256 || s->top_k > 64) return "E <= 256 and top_k <= 64 required";
+    if (s->num_shared > 8 || s->E + s->num_shared > MAX_GROUPS) return "num_shared <= 8 and E + num_shared <= 256 required";
+    const int64_t lim = (int64_t)1 << 32;
+    const int64_t R = (int64_t)s->T * s->top_k, Rs = (int64_t)s->T * s->num_shared;
+    if (R >= ((int64_t)1 << 31) / 2) return "T * top_k too large";
+    if (R * s->H * 2 >= lim || (R + Rs) * s->F * 2 >= lim || (int64_t)s->H * s->F * 2 >= lim)
+        return "a matrix reaches 4 GiB";
+    *st = MOE_OK;
+    return nullptr;
+}
+
+inline size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// Workspace layout: fixed order, every region 256-byte aligned.
+struct Layout {
+    size_t topk_idx, topk_w, offsets, perm, inv_perm, row_token, chunk_counts, plan, descs, h, y_perm, y_shared, total;
+};
+
+Layout make_layout(const moe_shape& s) {
+    Layout L;
+    const size_t R = (size_t)s.T * s.top_k, Rs = (size_t)s.T * s.num_shared;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+    L.topk_idx = take(R * 4);
+    L.topk_w = take(R * 4);
+    L.offsets = take(((size_t)s.E + 1) * 4);
+    L.perm = take(R * 4);
+    L.inv_perm = take(R * 4);
+    L.row_token = take(R * 4);
+    L.chunk_counts = take((size_t)permute_chunks(s) * s.E * 4);
+    L.plan = take(sizeof(PlanHeader));
+    L.descs = take((size_t)max_mtiles(s) * sizeof(TileDesc));
+    L.h = take((R + Rs) * s.F * 2);
+    L.y_perm = take(R * s.H * 2);
+    L.y_shared = take(Rs ? (size_t)s.T * s.H * 2 : 0);
+    L.total = o;
+    return L;
+}
+
+moe_status check_common(moe_ctx* c, const moe_shape* s) {
+    if (!c) return MOE_E_ARG;
+    c->err[0] = 0;
+    moe_status st;
+    if (const char* why = shape_problem(s, &st)) return fail(c, st, "%s", why);
+    HIP_TRY(c, hipSetDevice(c->device));
+    return MOE_OK;
+}
+
+moe_status check_ws(moe_ctx* c, const moe_shape* s, const void* ws, size_t bytes) {
+    if (!ws) return fail(c, MOE_E_ARG, "workspace is NULL");
+    if ((uintptr_t)ws & 255) return fail(c, MOE_E_ARG, "workspace must be 256-byte aligned");
+    const size_t need = make_layout(*s).total;
+    if (bytes < need) return fail(c, MOE_E_WORKSPACE, "workspace %zu bytes < required %zu", bytes, need);
+    return MOE_OK;
+}
+
+// ---- profiling helpers --------------------------------------------------------------------
+hipEvent_t get_event(moe_ctx* c) {
+    if (!c->pool.empty()) { hipEvent_t e = c->pool.back(); c->pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+struct StageTimer {
+    moe_ctx* c; hipStream_t st; int stage; hipEvent_t a = nullptr, b = nullptr;
+    StageTimer(moe_ctx* c_, hipStream_t st_, int stage_) : c(c_), st(st_), stage(stage_) {
+        if (c->prof && (int)c->recs.size() < PROF_MAX) {
+            a = get_event(c); b = get_event(c);
+            if (a && b) (void)hipEventRecord(a, st);
+        }
+    }
+    ~StageTimer() {
+        if (a && b) { (void)hipEventRecord(b, st); c->recs.push_back({stage, a, b}); }
+    }
+};
+
+// ---- weight pointer tables ----------------------------------------------------------------
+// Returns the device table holding [w1p | w3p | w2p] (MAX_GROUPS entries each); uploads only
+// when the caller's pointers differ from the last upload.
+moe_status weight_table(moe_ctx* c, int n, const void* const* w1, const void* const* w3, const void* const* w2,
+                        hipStream_t st, void*** out) {
+    if (!w1 || !w3 || !w2) return fail(c, MOE_E_ARG, "weight pointer table is NULL");
+    for (int i = 0; i < n; ++i)
+        if (!w1[i] || !w3[i] || !w2[i]) return fail(c, MOE_E_ARG, "weight pointer %d is NULL", i);
+    bool same = c->tab_cur >= 0 && c->tab_n == n;
+    if (same)
+        for (int i = 0; i < n && same; ++i)
+            same = c->tab_shadow[i] == w1[i] && c->tab_shadow[MAX_GROUPS + i] == w3[i] &&
+                   c->tab_shadow[2 * MAX_GROUPS + i] == w2[i];
+    if (!same) {
+        const int slot = c->tab_next;
+        c->tab_next = (slot + 1) % TABLE_SLOTS;
+        HIP_TRY(c, hipEventSynchronize(c->tab_done[slot]));  // the slot's previous upload has finished
+        for (int i = 0; i < n; ++i) {
+            c->h_tab[slot][i] = const_cast<void*>(w1[i]);
+            c->h_tab[slot][MAX_GROUPS + i] = const_cast<void*>(w3[i]);
+            c->h_tab[slot][2 * MAX_GROUPS + i] = const_cast<void*>(w2[i]);
+            c->tab_shadow[i] = w1[i];
+            c->tab_shadow[MAX_GROUPS + i] = w3[i];
+            c->tab_shadow[2 * MAX_GROUPS + i] = w2[i];
+        }
+        HIP_TRY(c, hipMemcpyAsync(c->d_tab[slot], c->h_tab[slot], 3 * MAX_GROUPS * sizeof(void*),
+                                  hipMemcpyHostToDevice, st));
+        HIP_TRY(c, hipEventRecord(c->tab_done[slot], st));
+        c->tab_cur = slot;
+        c->tab_n = n;
+    }
+    *out = c->d_tab[c->tab_cur];
+    return MOE_OK;
+}
+
+moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int32_t* row_token, const void* x,
+                   const int32_t* offsets, void** tab, char* ws, void* h, void* y_perm, void* y_shared,
+                   hipStream_t st) {
+    const Layout L = make_layout(s);
+    PlanHeader* plan = (PlanHeader*)(ws + L.plan);
+    TileDesc* descs = (TileDesc*)(ws + L.descs);
+    const size_t R = (size_t)s.T * s.top_k;
+    {
+        StageTimer tm(c, st, MOE_STAGE_PLAN);
+        HIP_TRY(c, launch_ffn_plan(s, offsets, plan, descs, c->gemm.small_tiles, c->gemm.wave_rows, st));
+    }
+    GemmArgs a;
+    memset(&a, 0, sizeof(a));
+    a.descs = descs;
+    a.plan = plan;
+    a.T = s.T;
+    a.max_mtiles = (int)max_mtiles(s);
+    a.group_m = c->gemm.group_m;
+    a.xcd_remap = c->gemm.xcd_remap;
+    a.small_tiles = c->gemm.small_tiles;
+    // GEMM 1: [rows, H] x W1p/W3p [F, H] -> h [rows, F]
+    a.a_routed = (const char*)(row_token ? x : x_perm);
+    a.a_shared = (const char*)x;
+    a.row_token = row_token;
+    a.w_a = (const void* const*)tab;
+    a.w_b = (const void* const*)(tab + MAX_GROUPS);
+    a.out_routed = (char*)h;
+    a.out_shared = (char*)h + R * s.F * 2;
+    a.K = s.H;
+    a.N = s.F;
+    a.nseg_shared = 1;
+    a.n_tiles = (s.F + 127) / 128;
+    {
+        StageTimer tm(c, st, MOE_STAGE_FFN_GATE_UP);
+        HIP_TRY(c, launch_ffn_gemm(true, a, c->gemm, st));
+    }
+    // GEMM 2: h [rows, F] x W2p [H, F] -> y [rows, H]
+    a.a_routed = (const char*)h;
+    a.a_shared = (const char*)h + R * s.F * 2;
+    a.row_token = nullptr;
+    a.w_a = (const void* const*)(tab + 2 * MAX_GROUPS);
+    a.w_b = nullptr;
+    a.out_routed = (char*)y_perm;
+    a.out_shared = (char*)y_shared;
+    a.K = s.F;
+    a.N = s.H;
+    a.nseg_shared = s.num_shared > 0 ? s.num_shared : 1;
+    a.n_tiles = (s.H + 255) / 256;
+    {
+        StageTimer tm(c, st, MOE_STAGE_FFN_DOWN);
+        HIP_TRY(c, launch_ffn_gemm(false, a, c->gemm, st));
+    }
+    return MOE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+moe_status moe_create(moe_ctx** out, int device) {
+    if (!out) return MOE_E_ARG;
+    *out = nullptr;
+    if (hipSetDevice(device) != hipSuccess) return MOE_E_HIP;
+    moe_ctx* c = new moe_ctx();
+    c->device = device;
+    c->tab_shadow.assign(3 * MAX_GROUPS, nullptr);
+    bool ok = ffn_gemm_init() == hipSuccess;
+    for (int i = 0; i < TABLE_SLOTS && ok; ++i) {
+        ok = hipMalloc((void**)&c->d_tab[i], 3 * MAX_GROUPS * sizeof(void*)) == hipSuccess &&
+             hipHostMalloc((void**)&c->h_tab[i], 3 * MAX_GROUPS * sizeof(void*), hipHostMallocDefault) == hipSuccess &&
+             hipEventCreateWithFlags(&c->tab_done[i], hipEventDisableTiming) == hipSuccess;
+    }
+    if (!ok) { moe_destroy(c); return MOE_E_HIP; }
+    *out = c;
+    return MOE_OK;
+}
+
+void moe_destroy(moe_ctx* c) {
+    if (!c) return;
+    (void)hipSetDevice(c->device);
+    (void)hipDeviceSynchronize();
+    for (int i = 0; i < TABLE_SLOTS; ++i) {
+        if (c->d_tab[i]) (void)hipFree(c->d_tab[i]);
+        if (c->h_tab[i]) (void)hipHostFree(c->h_tab[i]);
+        if (c->tab_done[i]) (void)hipEventDestroy(c->tab_done[i]);
+    }
+    for (auto& r : c->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+    for (auto e : c->pool) (void)hipEventDestroy(e);
+    delete c;
+}
+
+const char* moe_last_error(const moe_ctx* c) { return c ? c->err : "context is NULL"; }
+
+size_t moe_workspace_bytes(const moe_shape* s) {
+    moe_status st;
+    if (shape_problem(s, &st)) return 0;
+    return make_layout(*s).total;
+}
+
+moe_status moe_set_option(moe_ctx* c, const char* key, int32_t v) {
+    if (!c || !key) return MOE_E_ARG;
+    c->err[0] = 0;
+    if (!strcmp(key, "gemm_wave_rows") && (v == 1 || v == 2)) { c->gemm.wave_rows = v; return MOE_OK; }
+    if (!strcmp(key, "gemm_group_m") && v >= 1 && v <= 64) { c->gemm.group_m = v; return MOE_OK; }
+    if (!strcmp(key, "xcd_remap") && (v == 0 || v == 1)) { c->gemm.xcd_remap = v; return MOE_OK; }
+    if (!strcmp(key, "small_tiles") && (v == 0 || v == 1)) { c->gemm.small_tiles = v; return MOE_OK; }
+    return fail(c, MOE_E_ARG, "unknown option or value out of range: %s=%d", key, (int)v);
+}
+
+moe_status moe_pack_weight(moe_ctx* c, const void* w, int32_t rows, int32_t cols, void* packed, void* stream) {
+    if (!c) return MOE_E_ARG;
+    c->err[0] = 0;
+    if (!w || !packed || w == packed) return fail(c, MOE_E_ARG, "pack: NULL or aliased buffers");
+    if (rows < 8 || cols < 8 || rows % 8 || cols % 8) return fail(c, MOE_E_ARG, "pack: rows, cols must be positive multiples of 8");
+    if ((int64_t)rows * cols * 2 >= ((int64_t)1 << 32)) return fail(c, MOE_E_UNSUPPORTED, "pack: matrix reaches 4 GiB");
+    HIP_TRY(c, hipSetDevice(c->device));
+    HIP_TRY(c, launch_transpose(w, rows, cols, packed, (hipStream_t)stream));
+    return MOE_OK;
+}
+
+moe_status moe_route(moe_ctx* c, const moe_shape* s, const void* x, const void* wg, const float* bias,
+                     int32_t* idx, float* w, float* logits, void* stream) {
+    if (moe_status st = check_common(c, s)) return st;
+    if (!x || !wg || !idx || !w) return fail(c, MOE_E_ARG, "route: NULL pointer");
+    hipStream_t hs = (hipStream_t)stream;
+    StageTimer tm(c, hs, MOE_STAGE_ROUTE);
+    HIP_TRY(c, launch_route(*s, x, wg, bias, idx, w, logits, hs));
+    return MOE_OK;
+}
+
+moe_status moe_permute(moe_ctx* c, const moe_shape* s, const void* x, const int32_t* idx, void* x_perm,
+                       int32_t* offsets, int32_t* perm, int32_t* inv_perm, int32_t* row_token, void* ws,
+                       size_t ws_bytes, void* stream) {
+    if (moe_status st = check_common(c, s)) return st;
+    if (!idx || !offsets || !perm || !inv_perm) return fail(c, MOE_E_ARG, "permute: NULL pointer");
+    if (x_perm && !x) return fail(c, MOE_E_ARG, "permute: x is NULL but x_perm was requested");
+    if (moe_status st = check_ws(c, s, ws, ws_bytes)) return st;
+    hipStream_t hs = (hipStream_t)stream;
+    const Layout L = make_layout(*s);
+    {
+        StageTimer tm(c, hs, MOE_STAGE_PERMUTE_INDEX);
+        HIP_TRY(c, launch_permute_index(*s, idx, (int32_t*)((char*)ws + L.chunk_counts), offsets, perm, inv_perm,
+                                        row_token, hs));
+    }
+    if (x_perm) {
+        StageTimer tm(c, hs, MOE_STAGE_PERMUTE_GATHER);
+        HIP_TRY(c, launch_permute_gather(*s, x, perm, x_perm, hs));
+    }
+    return MOE_OK;
+}
+
+moe_status moe_grouped_ffn(moe_ctx* c, const moe_shape* s, const void* x_perm, const int32_t* row_token,
+                           const void* x, const int32_t* offsets, const void* const* w1p, const void* const* w3p,
+                           const void* const* w2p, void* h, void* y_perm, void* y_shared, void* ws, size_t ws_bytes,
+                           void* stream) {
+    if (moe_status st = check_common(c, s)) return st;
+    if (!offsets || !h || !y_perm) return fail(c, MOE_E_ARG, "grouped_ffn: NULL pointer");
+    if (!row_token && !x_perm) return fail(c, MOE_E_ARG, "grouped_ffn: need x_perm or row_token");
+    if ((row_token || s->num_shared > 0) && !x) return fail(c, MOE_E_ARG, "grouped_ffn: x is NULL");
+    if ((s->num_shared > 0) != (y_shared != nullptr)) return fail(c, MOE_E_ARG, "grouped_ffn: y_shared must be given iff num_shared > 0");
+    if (moe_status st = check_ws(c, s, ws, ws_bytes)) return st;
+    hipStream_t hs = (hipStream_t)stream;
+    void** tab = nullptr;
+    if (moe_status st = weight_table(c, s->E + s->num_shared, w1p, w3p, w2p, hs, &tab)) return st;
+    return run_ffn(c, *s, x_perm, row_token, x, offsets, tab, (char*)ws, h, y_perm, y_shared, hs);
+}
+
+moe_status moe_combine(moe_ctx* c, const moe_shape* s, const void* y_perm, const int32_t* inv_perm, const float* w,
+                       const void* y_shared, void* out, void* stream) {
+    if (moe_status st = check_common(c, s)) return st;
+    if (!y_perm || !inv_perm || !w || !out) return fail(c, MOE_E_ARG, "combine: NULL pointer");
+    hipStream_t hs = (hipStream_t)stream;
+    StageTimer tm(c, hs, MOE_STAGE_COMBINE);
+    HIP_TRY(c, launch_combine(*s, y_perm, inv_perm, w, y_shared, out, hs));
+    return MOE_OK;
+}
+
+moe_status moe_layer(moe_ctx* c, const moe_shape* s, const void* x, const void* wg, const float* bias,
+                     const void* const* w1p, const void* const* w3p, const void* const* w2p, void* out, void* ws,
+                     size_t ws_bytes, void* stream) {
+    if (moe_status st = check_common(c, s)) return st;
+    if (!x || !wg || !out) return fail(c, MOE_E_ARG, "layer: NULL pointer");
+    if (moe_status st = check_ws(c, s, ws, ws_bytes)) return st;
+    hipStream_t hs = (hipStream_t)stream;
+    void** tab = nullptr;
+    if (moe_status st = weight_table(c, s->E + s->num_shared, w1p, w3p, w2p, hs, &tab)) return st;
+    const Layout L = make_layout(*s);
+    char* w8 = (char*)ws;
+    int32_t* idx = (int32_t*)(w8 + L.topk_idx);
+    float* tw = (float*)(w8 + L.topk_w);
+    int32_t* offsets = (int32_t*)(w8 + L.offsets);
+    int32_t* perm = (int32_t*)(w8 + L.perm);
+    int32_t* inv_perm = (int32_t*)(w8 + L.inv_perm);
+    int32_t* row_token = (int32_t*)(w8 + L.row_token);
+    void* y_shared = s->num_shared > 0 ? (void*)(w8 + L.y_shared) : nullptr;
+    {
+        StageTimer tm(c, hs, MOE_STAGE_ROUTE);
+        HIP_TRY(c, launch_route(*s, x, wg, bias, idx, tw, nullptr, hs));
+    }
+    {
+        StageTimer tm(c, hs, MOE_STAGE_PERMUTE_INDEX);
+        HIP_TRY(c, launch_permute_index(*s, idx, (int32_t*)(w8 + L.chunk_counts), offsets, perm, inv_perm, row_token, hs));
+    }
+    if (moe_status st = run_ffn(c, *s, nullptr, row_token, x, offsets, tab, w8, w8 + L.h, w8 + L.y_perm, y_shared, hs))
+        return st;
+    {
+        StageTimer tm(c, hs, MOE_STAGE_COMBINE);
+        HIP_TRY(c, launch_combine(*s, w8 + L.y_perm, inv_perm, tw, y_shared, out, hs));
+    }
+    return MOE_OK;
+}
+
+moe_status moe_layer_views(const moe_shape* s, void* ws, int32_t** idx, float** w, int32_t** offsets,
+                           int32_t** inv_perm) {
+    moe_status st;
+    if (shape_problem(s, &st)) return st;
+    if (!ws) return MOE_E_ARG;
+    const Layout L = make_layout(*s);
+    char* w8 = (char*)ws;
+    if (idx) *idx = (int32_t*)(w8 + L.topk_idx);
+    if (w) *w = (float*)(w8 + L.topk_w);
+    if (offsets) *offsets = (int32_t*)(w8 + L.offsets);
+    if (inv_perm) *inv_perm = (int32_t*)(w8 + L.inv_perm);
+    return MOE_OK;
+}
+
+moe_status moe_profile_enable(moe_ctx* c, int32_t on) {
+    if (!c) return MOE_E_ARG;
+    c->prof = on != 0;
+    return MOE_OK;
+}
+
+moe_status moe_profile_read(moe_ctx* c, double* ms_sum, int32_t* launches) {
+    if (!c || !ms_sum || !launches) return MOE_E_ARG;
+    c->err[0] = 0;
+    for (int i = 0; i < MOE_STAGE_COUNT; ++i) { ms_sum[i] = 0.0; launches[i] = 0; }
+    for (auto& r : c->recs) {
+        HIP_TRY(c, hipEventSynchronize(r.b));
+        float ms = 0.f;
+        HIP_TRY(c, hipEventElapsedTime(&ms, r.a, r.b));
+        ms_sum[r.stage] += ms;
+        launches[r.stage] += 1;
+        c->pool.push_back(r.a);
+        c->pool.push_back(r.b);
+    }
+    c->recs.clear();
+    return MOE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,86 @@
+// Internal declarations shared by the kernels and the C-ABI layer (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "moe.h"
+
+namespace moe {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
+
+// One m-tile of the grouped GEMMs: rows [row0, row0+nrows) of one group.
+//   routed group : group = expert id, row0 = permuted row, srow = -1
+//   shared group : group = E + s,     row0 = first token,  srow = s * T (row offset inside the shared region)
+struct TileDesc {
+    int32_t group;
+    int32_t row0;
+    int32_t nrows;
+    int32_t srow;
+};
+
+struct PlanHeader {
+    int32_t n_gate_up;  // tiles of GEMM 1 (routed + every shared expert)
+    int32_t n_down;     // tiles of GEMM 2 (routed + shared expert 0; shared experts are K-concatenated)
+    int32_t pad[2];
+};
+
+struct GemmArgs {
+    const char* a_routed;      // GEMM1: x_perm, or x when row_token != nullptr; GEMM2: h
+    const char* a_shared;      // GEMM1: x; GEMM2: h + R*F
+    const int32_t* row_token;  // GEMM1 gather map or nullptr
+    const void* const* w_a;    // device table of packed weights: GEMM1 W1p, GEMM2 W2p
+    const void* const* w_b;    // GEMM1 W3p
+    char* out_routed;          // GEMM1: h; GEMM2: y_perm
+    char* out_shared;          // GEMM1: h + R*F; GEMM2: y_shared
+    const TileDesc* descs;
+    const PlanHeader* plan;
+    int32_t K, N;              // GEMM1: K=H, N=F; GEMM2: K=F, N=H
+    int32_t T;
+    int32_t nseg_shared;       // GEMM2: num_shared (K-concatenation); GEMM1: 1
+    int32_t n_tiles;           // tiles along N
+    int32_t max_mtiles;        // grid = max_mtiles * n_tiles
+    int32_t group_m;
+    int32_t xcd_remap;
+    int32_t small_tiles;       // 1: a short tail tile runs the 128/64/32-row variant
+};
+
+struct GemmConfig {
+    int wave_rows;    // 1 or 2
+    int group_m;
+    int xcd_remap;
+    int small_tiles;
+};
+
+// Upper bound on the number of m-tiles for any routing outcome.
+inline int64_t max_mtiles(const moe_shape& s) {
+    const int64_t R = (int64_t)s.T * s.top_k;
+    return R / 256 + s.E + (int64_t)s.num_shared * ((s.T + 255) / 256);
+}
+
+// ---- launchers (each only enqueues on `st`; returns the launch status) ----
+hipError_t launch_route(const moe_shape& s, const void* x, const void* wg, const float* bias, int32_t* idx,
+                        float* w, float* logits, hipStream_t st);
+
+constexpr int PERMUTE_CHUNK_TOKENS = 256;
+inline int permute_chunks(const moe_shape& s) { return (s.T + PERMUTE_CHUNK_TOKENS - 1) / PERMUTE_CHUNK_TOKENS; }
+hipError_t launch_permute_index(const moe_shape& s, const int32_t* idx, int32_t* chunk_counts, int32_t* offsets,
+                                int32_t* perm, int32_t* inv_perm, int32_t* row_token, hipStream_t st);
+hipError_t launch_permute_gather(const moe_shape& s, const void* x, const int32_t* perm, void* x_perm,
+                                 hipStream_t st);
+
+hipError_t launch_ffn_plan(const moe_shape& s, const int32_t* offsets, PlanHeader* plan, TileDesc* descs,
+                           int small_tiles, int wave_rows, hipStream_t st);
+hipError_t launch_ffn_gemm(bool gated, const GemmArgs& a, const GemmConfig& cfg, hipStream_t st);
+hipError_t ffn_gemm_init();  // one-time function attributes (dynamic LDS size)
+
+hipError_t launch_combine(const moe_shape& s, const void* y_perm, const int32_t* inv_perm, const float* w,
+                          const void* y_shared, void* out, hipStream_t st);
+hipError_t launch_transpose(const void* in, int rows, int cols, void* out, hipStream_t st);
+
+}  // namespace moe

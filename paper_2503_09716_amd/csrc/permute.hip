@@ -1,0 +1,174 @@
+// Permutation of (token, rank) pairs into per-expert contiguous groups: histogram, prefix
+// sums, stable placement, and the coalesced row gather.  (Sec. 2: each token is processed by
+// its k selected experts; Sec. 4.3: the per-expert token counts are only known at run time.)
+//
+// Canonical order = ascending expert id, then ascending token id, so the result is unique
+// and every run is bit-identical.  Tokens are cut into chunks of PERMUTE_CHUNK_TOKENS; one
+// wavefront owns one chunk:
+//   count : per-chunk per-expert histogram
+//   scan  : per-expert exclusive prefix over chunks, then exclusive prefix over experts
+//   place : the wavefront walks its chunk 64 tokens at a time; for every expert a ballot
+//           over the 64 lanes gives each matching token its rank (popcount of lower lanes);
+//           the running per-expert cursors stay in registers (lane e%64 owns expert e)
+//   gather: x_perm[r,:] = x[perm[r]/k,:] in 16-byte pieces, one row per wavefront pass
+#include "common.h"
+
+namespace moe {
+namespace {
+
+constexpr int MAX_E = 256;
+
+__global__ __launch_bounds__(64) void permute_count_kernel(const int32_t* __restrict__ idx, int T, int k, int E,
+                                                           int32_t* __restrict__ chunk_counts) {
+    __shared__ int cnt[MAX_E];
+    const int lane = threadIdx.x, chunk = blockIdx.x;
+    for (int e = lane; e < E; e += 64) cnt[e] = 0;
+    __syncthreads();
+    const int t0 = chunk * PERMUTE_CHUNK_TOKENS;
+    const int t1 = min(T, t0 + PERMUTE_CHUNK_TOKENS);
+    const int n = (t1 - t0) * k;
+    const int32_t* p = idx + (size_t)t0 * k;
+    for (int i = lane; i < n; i += 64) {
+        const int e = p[i];
+        if ((unsigned)e < (unsigned)E) atomicAdd(&cnt[e], 1);  // integer LDS counters: order-independent
+    }
+    __syncthreads();
+    for (int e = lane; e < E; e += 64) chunk_counts[(size_t)chunk * E + e] = cnt[e];
+}
+
+// chunk_counts[c][e] -> exclusive prefix over c (in place); offsets[e] = exclusive prefix over experts.
+__global__ __launch_bounds__(256) void permute_scan_kernel(int32_t* __restrict__ chunk_counts, int nchunks, int E,
+                                                           int32_t* __restrict__ offsets) {
+    __shared__ int total[MAX_E];
+    const int tid = threadIdx.x;
+    for (int e = tid; e < E; e += 256) {
+        int run = 0;
+        for (int c0 = 0; c0 < nchunks; c0 += 16) {
+            int v[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) v[u] = (c0 + u < nchunks) ? chunk_counts[(size_t)(c0 + u) * E + e] : 0;
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                if (c0 + u < nchunks) chunk_counts[(size_t)(c0 + u) * E + e] = run;
+                run += v[u];
+            }
+        }
+        total[e] = run;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        for (int e = 0; e < E; ++e) {
+            offsets[e] = run;
+            run += total[e];
+        }
+        offsets[E] = run;
+    }
+}
+
+// One 64-token step of the placement.  base[i] of lane l is the next free row of expert
+// i*64 + l; it lives in registers so the loop needs neither LDS nor barriers.
+template <int K>
+__device__ __forceinline__ void place_step(const int32_t* __restrict__ idx, int t, bool valid, int k_rt, int E,
+                                           int lane, int (&base)[MAX_E / 64], int32_t* __restrict__ perm,
+                                           int32_t* __restrict__ inv_perm, int32_t* __restrict__ row_token) {
+    const int k = K > 0 ? K : k_rt;
+    constexpr int KMAX = K > 0 ? K : 1;
+    int my[KMAX];
+    if (K > 0) {
+#pragma unroll
+        for (int j = 0; j < KMAX; ++j) my[j] = valid ? idx[(size_t)t * k + j] : -1;
+    }
+    const unsigned long long lt = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int i = 0; i < MAX_E / 64; ++i) {
+        for (int el = 0; el < 64; ++el) {
+            const int e = i * 64 + el;
+            if (e >= E) break;
+            int hit = -1;
+            if (K > 0) {
+#pragma unroll
+                for (int j = 0; j < KMAX; ++j)
+                    if (my[j] == e) hit = j;
+            } else if (valid) {
+                for (int j = 0; j < k; ++j)
+                    if (idx[(size_t)t * k + j] == e) hit = j;
+            }
+            const unsigned long long mask = __ballot(hit >= 0);
+            if (mask == 0ull) continue;  // wave-uniform
+            const int b = __builtin_amdgcn_readlane(base[i], el);
+            if (hit >= 0) {
+                const int slot = b + __popcll(mask & lt);
+                perm[slot] = t * k + hit;
+                inv_perm[(size_t)t * k + hit] = slot;
+                if (row_token) row_token[slot] = t;
+            }
+            if (lane == el) base[i] += __popcll(mask);
+        }
+    }
+}
+
+__global__ __launch_bounds__(64) void permute_place_kernel(const int32_t* __restrict__ idx, int T, int k, int E,
+                                                           const int32_t* __restrict__ chunk_prefix,
+                                                           const int32_t* __restrict__ offsets,
+                                                           int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm,
+                                                           int32_t* __restrict__ row_token) {
+    const int lane = threadIdx.x, chunk = blockIdx.x;
+    int base[MAX_E / 64];
+#pragma unroll
+    for (int i = 0; i < MAX_E / 64; ++i) {
+        const int e = i * 64 + lane;
+        base[i] = e < E ? offsets[e] + chunk_prefix[(size_t)chunk * E + e] : 0;
+    }
+    const int t0 = chunk * PERMUTE_CHUNK_TOKENS;
+    for (int s = 0; s < PERMUTE_CHUNK_TOKENS; s += 64) {
+        if (t0 + s >= T) break;
+        const int t = t0 + s + lane;
+        const bool valid = t < T;
+        switch (k) {
+            case 1: place_step<1>(idx, t, valid, k, E, lane, base, perm, inv_perm, row_token); break;
+            case 2: place_step<2>(idx, t, valid, k, E, lane, base, perm, inv_perm, row_token); break;
+            case 4: place_step<4>(idx, t, valid, k, E, lane, base, perm, inv_perm, row_token); break;
+            case 6: place_step<6>(idx, t, valid, k, E, lane, base, perm, inv_perm, row_token); break;
+            case 8: place_step<8>(idx, t, valid, k, E, lane, base, perm, inv_perm, row_token); break;
+            default: place_step<0>(idx, t, valid, k, E, lane, base, perm, inv_perm, row_token); break;
+        }
+    }
+}
+
+// One wavefront copies one row per pass; 16 bytes per lane, consecutive lanes consecutive addresses.
+__global__ __launch_bounds__(256) void permute_gather_kernel(const uint4* __restrict__ x, const int32_t* __restrict__ perm,
+                                                             int R, int k, int row16, uint4* __restrict__ x_perm) {
+    const int lane = threadIdx.x & 63;
+    const int wave = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int nwaves = gridDim.x * 4;
+    for (int r = wave; r < R; r += nwaves) {
+        const int t = perm[r] / k;
+        const uint4* src = x + (size_t)t * row16;
+        uint4* dst = x_perm + (size_t)r * row16;
+        for (int c = lane; c < row16; c += 64) dst[c] = src[c];
+    }
+}
+
+}  // namespace
+
+hipError_t launch_permute_index(const moe_shape& s, const int32_t* idx, int32_t* chunk_counts, int32_t* offsets,
+                                int32_t* perm, int32_t* inv_perm, int32_t* row_token, hipStream_t st) {
+    const int nchunks = permute_chunks(s);
+    hipLaunchKernelGGL(permute_count_kernel, dim3(nchunks), dim3(64), 0, st, idx, s.T, s.top_k, s.E, chunk_counts);
+    hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(256), 0, st, chunk_counts, nchunks, s.E, offsets);
+    hipLaunchKernelGGL(permute_place_kernel, dim3(nchunks), dim3(64), 0, st, idx, s.T, s.top_k, s.E,
+                       (const int32_t*)chunk_counts, (const int32_t*)offsets, perm, inv_perm, row_token);
+    return hipGetLastError();
+}
+
+hipError_t launch_permute_gather(const moe_shape& s, const void* x, const int32_t* perm, void* x_perm,
+                                 hipStream_t st) {
+    const int R = s.T * s.top_k;
+    const int blocks = (R + 3) / 4 < 8192 ? (R + 3) / 4 : 8192;
+    hipLaunchKernelGGL(permute_gather_kernel, dim3(blocks), dim3(256), 0, st, (const uint4*)x, perm, R, s.top_k,
+                       s.H / 8, (uint4*)x_perm);
+    return hipGetLastError();
+}
+
+}  // namespace moe

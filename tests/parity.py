@@ -1,0 +1,163 @@
+"""Helpers shared by the GPU parity tests: run the HIP path through the binding, run the
+oracle on the same bytes, compare to the stated bars.
+
+Bars:  routing indices and the permutation bit-exact, except at reported top-k near-ties
+(oracle logit margin < 1e-5); routing weights to 1e-5 relative; FFN / layer output
+max-abs error <= 2e-2 x RMS(oracle output)."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import moe_oracle as orc
+from workloads import torch_bf16_to_u16
+
+TIE_MARGIN = 1e-5
+OUT_BAR = 2e-2
+W_RTOL = 1e-5
+
+
+def host_u16(t: torch.Tensor) -> np.ndarray:
+    return torch_bf16_to_u16(t)
+
+
+def compare_routing(gpu_idx: np.ndarray, gpu_w: np.ndarray, ref: dict, top_k: int):
+    """ref: oracle.route(..., want_logits=True) for the same tokens.  Returns a report; raises on an
+    unexcused mismatch.  A set mismatch at token t is excused iff the oracle's k-th and (k+1)-th
+    largest logits differ by < TIE_MARGIN; an order-only mismatch iff every displaced pair of
+    logits differs by < TIE_MARGIN."""
+    idx_o, w_o, logit = ref["idx"], ref["w"], ref["logits"]
+    n, E = logit.shape
+    bad = np.nonzero((gpu_idx != idx_o).any(axis=1))[0]
+    excused_set, excused_order = [], []
+    for t in bad:
+        so = np.sort(logit[t])[::-1]
+        same_set = set(gpu_idx[t].tolist()) == set(idx_o[t].tolist())
+        if same_set:
+            d = np.abs(logit[t, gpu_idx[t]] - logit[t, idx_o[t]]).max()
+            assert d < TIE_MARGIN, "token %d: order mismatch with logit gap %g" % (t, d)
+            excused_order.append(int(t))
+        else:
+            margin = so[top_k - 1] - so[top_k] if top_k < E else np.inf
+            assert margin < TIE_MARGIN, "token %d: top-k set mismatch with margin %g (gpu %s, oracle %s)" % (
+                t, margin, gpu_idx[t].tolist(), idx_o[t].tolist())
+            assert len(set(gpu_idx[t].tolist())) == top_k
+            excused_set.append(int(t))
+    good = np.setdiff1d(np.arange(n), bad)
+    if len(good):
+        np.testing.assert_allclose(gpu_w[good], w_o[good], rtol=W_RTOL, atol=1e-7)
+    so = np.sort(logit, axis=1)[:, ::-1]
+    near = int((so[:, top_k - 1] - so[:, top_k] < TIE_MARGIN).sum()) if top_k < E else 0
+    return {"tokens": int(n), "mismatch_set_excused": excused_set, "mismatch_order_excused": excused_order,
+            "near_ties_in_oracle": near}
+
+
+def output_report(out_gpu: np.ndarray, out_ref: np.ndarray):
+    """Error of a bf16 GPU result against the fp32 oracle, relative to the oracle's RMS."""
+    ref = out_ref.astype(np.float64)
+    got = out_gpu.astype(np.float64)
+    rms = float(np.sqrt((ref ** 2).mean()))
+    err = np.abs(got - ref)
+    rel = err / np.maximum(np.abs(ref), 1e-30)
+    big = np.abs(ref) > 0.1 * rms
+    ref_bf16 = torch.from_numpy(out_ref.astype(np.float32)).to(torch.bfloat16).float().numpy().astype(np.float64)
+    return {
+        "rms": rms,
+        "max_abs_over_rms": float(err.max() / rms) if rms > 0 else float(err.max()),
+        "max_abs_vs_bf16_rounded_oracle_over_rms": float(np.abs(got - ref_bf16).max() / rms) if rms > 0 else 0.0,
+        "rel_p50": float(np.median(rel[big])) if big.any() else 0.0,
+        "rel_p99": float(np.percentile(rel[big], 99)) if big.any() else 0.0,
+        "rel_max": float(rel[big].max()) if big.any() else 0.0,
+    }
+
+
+def assert_output(out_gpu: np.ndarray, out_ref: np.ndarray, what: str = "output"):
+    rep = output_report(out_gpu, out_ref)
+    assert rep["max_abs_over_rms"] <= OUT_BAR, "%s: max-abs error %.4g x RMS exceeds %.2g (%s)" % (
+        what, rep["max_abs_over_rms"], OUT_BAR, rep)
+    return rep
+
+
+class GpuLayer:
+    """One synthetic layer resident on the GPU with packed weights, plus host copies for the oracle."""
+
+    def __init__(self, moe, li, host_weights: bool = True):
+        from paper_2503_09716_amd import shape_of
+        self.moe, self.li, self.cfg = moe, li, li.cfg
+        self.shape = shape_of(li.cfg)
+        self.x, self.wg = li.x, li.wg
+        self.bias = None if li.bias is None else torch.from_numpy(li.bias).cuda()
+        self.w1p, self.w3p, self.w2p = moe.pack_experts(li.w1, li.w3, li.w2)
+        torch.cuda.synchronize()
+        self.ws = moe.new_workspace(self.shape)
+        self.tables = moe.tables(self.w1p, self.w3p, self.w2p)
+        if host_weights:
+            self.hx, self.hwg = host_u16(li.x), host_u16(li.wg)
+            self.hw1 = [host_u16(w) for w in li.w1]
+            self.hw3 = [host_u16(w) for w in li.w3]
+            self.hw2 = [host_u16(w) for w in li.w2]
+
+    def run_layer(self):
+        cfg = self.cfg
+        out = torch.empty((cfg.T, cfg.H), dtype=torch.bfloat16, device="cuda")
+        self.moe.layer(self.shape, self.x, self.wg, self.bias, self.w1p, self.w3p, self.w2p, out, self.ws,
+                       tables=self.tables)
+        torch.cuda.synchronize()
+        return out
+
+    def oracle_route(self, tokens=None):
+        cfg = self.cfg
+        return orc.route(self.hx, self.hwg, self.li.bias, cfg.top_k, cfg.renormalize, cfg.routed_scale,
+                         tokens=tokens, want_logits=True)
+
+    def oracle_layer(self, idx, w, tokens=None):
+        cfg = self.cfg
+        return orc.layer(self.hx, idx, w, self.hw1, self.hw3, self.hw2, cfg.E, cfg.num_shared, tokens=tokens)
+
+
+def check_layer_against_oracle(gl: GpuLayer, out: torch.Tensor, tokens=None, check_all_routing: bool = True):
+    """Full check of one moe_layer result.  tokens=None: every token through the oracle;
+    otherwise the FFN/combine part only for the listed tokens (routing still for all tokens
+    when check_all_routing)."""
+    cfg = gl.cfg
+    views = gl.moe.layer_views(gl.shape, gl.ws)
+    idx = views["topk_idx"].cpu().numpy()
+    w = views["topk_w"].cpu().numpy()
+    off = views["expert_offsets"].cpu().numpy()
+    inv = views["inv_perm"].cpu().numpy()
+    report = {}
+    # permutation: bit-exact against the oracle's stable counting sort of the GPU's own routing
+    o_off, o_perm, o_inv = orc.permute(idx, cfg.E)
+    np.testing.assert_array_equal(off, o_off)
+    np.testing.assert_array_equal(inv, o_inv)
+    cnt = np.diff(off)
+    report["rows_per_expert"] = {"max": int(cnt.max()), "mean": float(cnt.mean()), "min": int(cnt.min()),
+                                 "empty": int((cnt == 0).sum())}
+    # routing
+    rt_tokens = None if (check_all_routing or tokens is None) else tokens
+    ref = gl.oracle_route(rt_tokens)
+    sel = slice(None) if rt_tokens is None else rt_tokens
+    report["routing"] = compare_routing(idx[sel], w[sel], ref, cfg.top_k)
+    # FFN + combine: the oracle runs with the GPU's routing, so an excused near-tie cannot fail it
+    if tokens is None:
+        tokens = np.arange(cfg.T, dtype=np.int32)
+    tokens = np.asarray(tokens, dtype=np.int32)
+    out_ref = gl.oracle_layer(idx[tokens], w[tokens], tokens=tokens)
+    out_gpu = out[torch.from_numpy(tokens.astype(np.int64)).cuda()].float().cpu().numpy()
+    report["output"] = assert_output(out_gpu, out_ref, "layer output (%s)" % cfg.name)
+    return report
+
+
+def sample_tokens(idx: np.ndarray, E: int, n: int, seed: int) -> np.ndarray:
+    """n tokens: one routed to each non-empty expert, the rest uniformly at random."""
+    rng = np.random.default_rng(seed)
+    T = idx.shape[0]
+    chosen = []
+    flat_tok = np.repeat(np.arange(T), idx.shape[1])
+    flat_e = idx.reshape(-1)
+    order = rng.permutation(len(flat_e))
+    seen = np.full(E, -1, np.int64)
+    seen[flat_e[order]] = flat_tok[order]
+    chosen = [int(t) for t in seen if t >= 0]
+    rest = rng.permutation(T)[:max(0, n - len(chosen))]
+    return np.unique(np.concatenate([np.array(chosen, np.int64), rest])).astype(np.int32)
