@@ -1,0 +1,135 @@
+"""Benchmark of the MoE expert module on one MI355X.
+
+A step = one moe_layer call (route -> permute -> grouped SwiGLU FFN -> combine) over one
+synthetic accumulated batch that is already resident in HBM.  Prints ONE JSON line:
+tokens/s of the whole layer, the grouped-GEMM roofline (live HIP-event timings recorded by the
+library on the launch stream) and the CPU oracle timed on this machine's host cores.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(cfg, li, target_seconds: float = 12.0):
+    """The oracle as it stands, on a bounded sample of tokens of the same workload."""
+    import numpy as np
+    from oracle import moe_oracle as orc
+    from workloads import torch_bf16_to_u16 as u
+    hx, hwg = u(li.x), u(li.wg)
+    hw1 = [u(w) for w in li.w1]; hw3 = [u(w) for w in li.w3]; hw2 = [u(w) for w in li.w2]
+    threads = orc.num_threads()
+    rng = np.random.default_rng(cfg.seed)
+    order = rng.permutation(cfg.T).astype(np.int32)
+    done, t0 = 0, time.perf_counter()
+    while done < cfg.T:
+        tok = order[done:done + threads]
+        r = orc.route(hx, hwg, li.bias, cfg.top_k, cfg.renormalize, cfg.routed_scale, tokens=tok)
+        orc.layer(hx, r["idx"], r["w"], hw1, hw3, hw2, cfg.E, cfg.num_shared, tokens=tok)
+        done += len(tok)
+        if time.perf_counter() - t0 >= target_seconds:
+            break
+    dt = time.perf_counter() - t0
+    return {"value": done / dt, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": "%d seeded random tokens of %s through route + experts + combine, %.1f s" % (done, cfg.name, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--option", action="append", default=[], help="library tuning knob key=value")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2503_09716_amd import Moe, STAGES, shape_of
+    from workloads import get_config, make_layer_inputs
+
+    cfg = get_config(args.workload)
+    moe = Moe(0)
+    for kv in args.option:
+        k, v = kv.split("=")
+        moe.set_option(k, int(v))
+    li = make_layer_inputs(cfg, device="cuda")
+    shape = shape_of(cfg)
+    w1p, w3p, w2p = moe.pack_experts(li.w1, li.w3, li.w2)
+    bias = None if li.bias is None else torch.from_numpy(li.bias).cuda()
+    ws = moe.new_workspace(shape)
+    out = torch.empty((cfg.T, cfg.H), dtype=torch.bfloat16, device="cuda")
+    tables = moe.tables(w1p, w3p, w2p)
+    torch.cuda.synchronize()
+
+    def step():
+        moe.layer(shape, li.x, li.wg, bias, w1p, w3p, w2p, out, ws, tables=tables)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    moe.profile_enable(True)
+    moe.profile_read()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = moe.profile_read()
+    moe.profile_enable(False)
+
+    ms_per_step = dt / args.steps * 1e3
+    stage_ms = {s: (prof[s][0] / prof[s][1] if prof[s][1] else 0.0) for s in STAGES}
+    R, Rs = cfg.T * cfg.top_k, cfg.T * cfg.num_shared
+    flops_g1 = 4.0 * (R + Rs) * cfg.H * cfg.F
+    flops_g2 = 2.0 * (R + Rs) * cfg.H * cfg.F
+    g1_ms, g2_ms = stage_ms["ffn_gate_up"], stage_ms["ffn_down"]
+    achieved = flops_g1 / (g1_ms * 1e-3) / 1e12 if g1_ms > 0 else 0.0
+    ffn_tflops = (flops_g1 + flops_g2) / ((g1_ms + g2_ms) * 1e-3) / 1e12 if g1_ms + g2_ms > 0 else 0.0
+    views = moe.layer_views(shape, ws)
+    cnt = views["expert_offsets"].cpu().diff()
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic_%s.json" % cfg.name)
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get("ffn_gate_up_hbm_bytes_per_launch")
+
+    result = {
+        "metric": "expert-module tokens/s and grouped-FFN TFLOP/s (% bf16 MFMA peak), 1 GPU",
+        "value": cfg.T / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: T=%d H=%d F=%d E=%d top_k=%d shared=%d, weights resident in HBM" % (
+            cfg.name, cfg.T, cfg.H, cfg.F, cfg.E, cfg.top_k, cfg.num_shared),
+            "rows_per_expert": {"max": int(cnt.max()), "mean": float(cnt.float().mean()), "min": int(cnt.min())}},
+        "grouped_ffn_tflops": ffn_tflops,
+        "grouped_ffn_frac_of_bf16_peak": ffn_tflops / PEAK_BF16_TFLOPS,
+        "stage_ms": stage_ms,
+        "roofline": {"bound": "mfma", "kernel": "ffn_gemm_kernel<gated> (gate/up projection + SiLU-gate)",
+                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
+                     "avg_launch_ms": g1_ms, "flops_per_launch": flops_g1},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, li)
+    print(json.dumps(result))
+    moe.close()
+
+
+if __name__ == "__main__":
+    main()

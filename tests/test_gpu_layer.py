@@ -1,0 +1,144 @@
+"""GPU parity of the fused moe_layer call: every token against the oracle at small sizes, and
+the five full-size workloads (in the launch configuration bench.py times) on all tokens for
+routing and permutation and on sampled tokens for the FFN and combine."""
+import json
+import os
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import parity as P
+from workloads import get_config, make_layer_inputs, scaled_config, torch_bf16_to_u16
+
+pytestmark = pytest.mark.gpu
+
+OUT_DIR = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+
+
+@pytest.fixture(scope="module")
+def moe():
+    from paper_2503_09716_amd import Moe
+    m = Moe(0)
+    yield m
+    m.close()
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+SMALL = [
+    ("C1", {}),
+    ("C2", dict(T=300, H=256, F=448)),                       # ragged token count, F not a multiple of 128
+    ("C3", dict(T=515, H=192, F=256)),
+    ("C4", dict(T=640, H=256, F=192)),                       # 64 experts top-6 + 2 shared
+    ("C5", dict(T=900, H=320, F=128)),                       # 160 experts, log-Zipf skew, tiny groups
+    ("C5b", dict(T=400, H=128, F=128)),                      # most experts empty
+]
+
+
+@pytest.mark.parametrize("name,over", SMALL)
+def test_layer_all_tokens(moe, name, over):
+    cfg = scaled_config(name, **over) if over else get_config(name)
+    say("layer", cfg)
+    gl = P.GpuLayer(moe, make_layer_inputs(cfg, device="cuda"))
+    out = gl.run_layer()
+    rep = P.check_layer_against_oracle(gl, out)
+    say(json.dumps(rep))
+    # run-to-run determinism: prefix-sum placement and atomic-free combine give identical bits
+    out2 = gl.run_layer()
+    assert torch.equal(out.view(torch.int16), out2.view(torch.int16))
+
+
+def test_layer_everything_to_one_expert(moe):
+    """Worst-case skew: a huge bias sends every token's first choice to one expert; the declared
+    workspace must suffice (token counts are unknown until run time)."""
+    cfg = scaled_config("C1", T=700, H=128, F=128, E=8, top_k=2)
+    li = make_layer_inputs(cfg, device="cuda")
+    li.bias = np.zeros(cfg.E, np.float32)
+    li.bias[5] = 50.0
+    gl = P.GpuLayer(moe, li)
+    out = gl.run_layer()
+    rep = P.check_layer_against_oracle(gl, out)
+    assert rep["rows_per_expert"]["max"] == cfg.T
+    say(json.dumps(rep))
+
+
+def test_fused_equals_staged_bit_for_bit(moe):
+    cfg = scaled_config("C4", T=500, H=256, F=192)
+    gl = P.GpuLayer(moe, make_layer_inputs(cfg, device="cuda"), host_weights=False)
+    out = gl.run_layer()
+    sh = gl.shape
+    R = cfg.T * cfg.top_k
+    dev = "cuda"
+    idx = torch.empty((cfg.T, cfg.top_k), dtype=torch.int32, device=dev)
+    w = torch.empty((cfg.T, cfg.top_k), dtype=torch.float32, device=dev)
+    moe.route(sh, gl.x, gl.wg, gl.bias, idx, w, None)
+    x_perm = torch.empty((R, cfg.H), dtype=torch.bfloat16, device=dev)
+    off = torch.empty(cfg.E + 1, dtype=torch.int32, device=dev)
+    perm = torch.empty(R, dtype=torch.int32, device=dev); inv = torch.empty_like(perm)
+    ws = moe.new_workspace(sh)
+    moe.permute(sh, gl.x, idx, x_perm, off, perm, inv, None, ws)
+    h = torch.empty((R + cfg.T * cfg.num_shared, cfg.F), dtype=torch.bfloat16, device=dev)
+    y = torch.empty((R, cfg.H), dtype=torch.bfloat16, device=dev)
+    ysh = torch.empty((cfg.T, cfg.H), dtype=torch.bfloat16, device=dev)
+    moe.grouped_ffn(sh, x_perm, None, gl.x, off, gl.w1p, gl.w3p, gl.w2p, h, y, ysh, ws)
+    out2 = torch.empty_like(out)
+    moe.combine(sh, y, inv, w, ysh, out2)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), out2.view(torch.int16))
+    v = moe.layer_views(sh, gl.ws)
+    assert torch.equal(v["topk_idx"], idx) and torch.equal(v["topk_w"], w)
+    assert torch.equal(v["expert_offsets"], off) and torch.equal(v["inv_perm"], inv)
+
+
+def test_layer_metamorphic_exact(moe):
+    """Doubling W2 doubles the output bit-exactly; zero input gives zero output."""
+    cfg = scaled_config("C1", T=200, H=128, F=128)
+    li = make_layer_inputs(cfg, device="cuda")
+    a = P.GpuLayer(moe, li, host_weights=False).run_layer()
+    li2 = make_layer_inputs(cfg, device="cuda")
+    li2.w2 = [w * 2 for w in li2.w2]
+    b = P.GpuLayer(moe, li2, host_weights=False).run_layer()
+    assert torch.equal(a.float() * 2, b.float())
+    li3 = make_layer_inputs(cfg, device="cuda")
+    li3.x = torch.zeros_like(li3.x)
+    z = P.GpuLayer(moe, li3, host_weights=False).run_layer()
+    assert (z.float() == 0).all()
+
+
+FULL = [("C2", 96), ("C3", 64), ("C4", 160), ("C5", 224), ("C5b", 64)]
+
+
+@pytest.mark.parametrize("name,nsample", FULL)
+def test_layer_full_size_sampled(moe, name, nsample):
+    """Full-size workload: routing and permutation for ALL tokens, FFN + combine on a seeded sample
+    of tokens that covers every non-empty expert (tokens are independent, so per-token oracle
+    outputs are exact)."""
+    cfg = get_config(name)
+    t0 = time.time()
+    say("full", cfg)
+    li = make_layer_inputs(cfg, device="cuda")
+    gl = P.GpuLayer(moe, li)
+    say("  inputs + packing + host copies: %.1fs" % (time.time() - t0))
+    out = gl.run_layer()
+    assert torch.isfinite(out.float()).all()
+    idx = moe.layer_views(gl.shape, gl.ws)["topk_idx"].cpu().numpy()
+    tokens = P.sample_tokens(idx, cfg.E, nsample, cfg.seed)
+    t1 = time.time()
+    rep = P.check_layer_against_oracle(gl, out, tokens=tokens, check_all_routing=True)
+    rep["sampled_tokens"] = int(len(tokens))
+    rep["oracle_seconds"] = round(time.time() - t1, 1)
+    say(json.dumps(rep))
+    cnt = rep["rows_per_expert"]
+    if name == "C2":
+        assert cnt["max"] < 1.15 * cnt["mean"]              # large batches route near-uniformly (Sec. 4.2)
+    if name == "C5":
+        assert cnt["max"] > 10 * cnt["mean"]
+    if name == "C5b":
+        assert cnt["empty"] > 0
+    os.makedirs(OUT_DIR, exist_ok=True)
+    with open(os.path.join(OUT_DIR, "parity_%s.json" % name), "w") as f:
+        json.dump(rep, f)

@@ -1,0 +1,287 @@
+"""GPU parity of each staged C-ABI call against the CPU oracle, element by element, at sizes
+the oracle finishes in seconds but that span several tiles and ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe_oracle as orc
+import parity as P
+from workloads import get_config, make_layer_inputs, normal_bf16, scaled_config, torch_bf16_to_u16
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def moe():
+    from paper_2503_09716_amd import Moe
+    m = Moe(0)
+    yield m
+    m.close()
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+ROUTE_CASES = [
+    ("C1", {}),
+    ("C2", dict(T=777, H=512)),
+    ("C3", dict(T=300, H=256)),
+    ("C4", dict(T=1000, H=512)),
+    ("C5", dict(T=1500, H=1024)),
+    ("C5b", dict(T=257, H=256)),
+    ("C1", dict(T=1, H=64)),
+    ("C1", dict(T=33, H=64, E=8, top_k=8)),      # k = E
+    ("C4", dict(T=65, H=128, E=200, top_k=13)),   # E not a multiple of 32, odd k
+]
+
+
+@pytest.mark.parametrize("name,over", ROUTE_CASES)
+def test_route(moe, name, over):
+    from paper_2503_09716_amd import shape_of
+    cfg = scaled_config(name, **over) if over else get_config(name)
+    say("route", cfg)
+    li = make_layer_inputs(cfg, device="cuda", experts=False)
+    shape = shape_of(cfg)
+    idx = torch.empty((cfg.T, cfg.top_k), dtype=torch.int32, device="cuda")
+    w = torch.empty((cfg.T, cfg.top_k), dtype=torch.float32, device="cuda")
+    logits = torch.empty((cfg.T, cfg.E), dtype=torch.float32, device="cuda")
+    bias = None if li.bias is None else torch.from_numpy(li.bias).cuda()
+    moe.route(shape, li.x, li.wg, bias, idx, w, logits)
+    torch.cuda.synchronize()
+    ref = orc.route(torch_bf16_to_u16(li.x), torch_bf16_to_u16(li.wg), li.bias, cfg.top_k, cfg.renormalize,
+                    cfg.routed_scale, want_logits=True)
+    rep = P.compare_routing(idx.cpu().numpy(), w.cpu().numpy(), ref, cfg.top_k)
+    say(rep)
+    err = np.abs(logits.cpu().numpy() - ref["logits"]).max()
+    assert err < 5e-6, err
+    if cfg.renormalize:
+        np.testing.assert_allclose(w.sum(1).cpu().numpy(), cfg.routed_scale, atol=2e-6)
+    # without the optional logits output the result is the same, bit for bit
+    idx2 = torch.empty_like(idx); w2 = torch.empty_like(w)
+    moe.route(shape, li.x, li.wg, bias, idx2, w2, None)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, idx2) and torch.equal(w, w2)
+
+
+def test_route_exact_ties_pick_lowest_expert(moe):
+    from paper_2503_09716_amd import make_shape
+    T, H, E, k = 40, 64, 70, 3
+    x = normal_bf16(1, 0, (T, H), 1.0, "cuda")
+    wg = torch.zeros((H, E), dtype=torch.bfloat16, device="cuda")
+    idx = torch.empty((T, k), dtype=torch.int32, device="cuda")
+    w = torch.empty((T, k), dtype=torch.float32, device="cuda")
+    moe.route(make_shape(T, H, 64, E, k, 0, False), x, wg, None, idx, w, None)
+    torch.cuda.synchronize()
+    assert (idx.cpu().numpy() == np.arange(k)[None, :]).all()
+    np.testing.assert_allclose(w.cpu().numpy(), 1.0 / E, rtol=1e-6)
+
+
+def random_routing(rng, T, E, k, skew=None):
+    """Distinct experts per token.  skew = 'one': expert 0 stays empty, every token goes to expert 1,
+    and the top third of the expert ids is hit by a single token each (tiny groups)."""
+    if skew != "one":
+        return np.stack([rng.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
+    lo = np.arange(1, E - E // 3)
+    idx = np.stack([rng.permutation(lo)[:k] for _ in range(T)]).astype(np.int32)
+    for t in range(T):
+        if 1 not in idx[t]:
+            idx[t, 0] = 1
+    for i, e in enumerate(range(E - E // 3, E)):
+        if k > 1:
+            idx[i, 1] = e
+    return idx
+
+
+PERMUTE_CASES = [(256, 8, 2, None), (1000, 64, 6, None), (777, 160, 6, "one"), (1, 4, 1, None), (300, 5, 5, None),
+                 (2049, 37, 3, None)]
+
+
+@pytest.mark.parametrize("T,E,k,skew", PERMUTE_CASES)
+def test_permute(moe, T, E, k, skew):
+    from paper_2503_09716_amd import make_shape
+    say("permute", T, E, k, skew)
+    H = 128
+    rng = np.random.default_rng(T * 7 + E)
+    idx_h = random_routing(rng, T, E, k, skew)
+    shape = make_shape(T, H, 64, E, k)
+    x = normal_bf16(3, 0, (T, H), 1.0, "cuda")
+    idx = torch.from_numpy(idx_h).cuda()
+    R = T * k
+    x_perm = torch.empty((R, H), dtype=torch.bfloat16, device="cuda")
+    off = torch.empty(E + 1, dtype=torch.int32, device="cuda")
+    perm = torch.empty(R, dtype=torch.int32, device="cuda")
+    inv = torch.empty(R, dtype=torch.int32, device="cuda")
+    rtok = torch.empty(R, dtype=torch.int32, device="cuda")
+    ws = moe.new_workspace(shape)
+    moe.permute(shape, x, idx, x_perm, off, perm, inv, rtok, ws)
+    torch.cuda.synchronize()
+    o_off, o_perm, o_inv = orc.permute(idx_h, E)
+    np.testing.assert_array_equal(off.cpu().numpy(), o_off)
+    np.testing.assert_array_equal(perm.cpu().numpy(), o_perm)
+    np.testing.assert_array_equal(inv.cpu().numpy(), o_inv)
+    np.testing.assert_array_equal(rtok.cpu().numpy(), o_perm // k)
+    xh = torch_bf16_to_u16(x)
+    np.testing.assert_array_equal(torch_bf16_to_u16(x_perm), xh[o_perm // k])
+    # every token appears exactly k times
+    np.testing.assert_array_equal(np.bincount(perm.cpu().numpy() // k, minlength=T), np.full(T, k))
+
+
+def run_ffn_stage(moe, cfg, idx_h, wave_rows=2, small_tiles=1, use_row_token=False):
+    """Runs moe_permute + moe_grouped_ffn for a given routing; returns (y_perm, y_shared, perm, li)."""
+    from paper_2503_09716_amd import shape_of
+    shape = shape_of(cfg)
+    li = make_layer_inputs(cfg, device="cuda")
+    w1p, w3p, w2p = moe.pack_experts(li.w1, li.w3, li.w2)
+    R = cfg.T * cfg.top_k
+    idx = torch.from_numpy(idx_h).cuda()
+    x_perm = torch.empty((R, cfg.H), dtype=torch.bfloat16, device="cuda")
+    off = torch.empty(cfg.E + 1, dtype=torch.int32, device="cuda")
+    perm = torch.empty(R, dtype=torch.int32, device="cuda")
+    inv = torch.empty(R, dtype=torch.int32, device="cuda")
+    rtok = torch.empty(R, dtype=torch.int32, device="cuda")
+    ws = moe.new_workspace(shape)
+    moe.permute(shape, li.x, idx, x_perm, off, perm, inv, rtok, ws)
+    h = torch.empty((R + cfg.T * cfg.num_shared, cfg.F), dtype=torch.bfloat16, device="cuda")
+    y = torch.full((R, cfg.H), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ysh = torch.full((cfg.T, cfg.H), float("nan"), dtype=torch.bfloat16, device="cuda") if cfg.num_shared else None
+    moe.set_option("gemm_wave_rows", wave_rows)
+    moe.set_option("small_tiles", small_tiles)
+    try:
+        moe.grouped_ffn(shape, None if use_row_token else x_perm, rtok if use_row_token else None, li.x, off,
+                        w1p, w3p, w2p, h, y, ysh, ws)
+        torch.cuda.synchronize()
+    finally:
+        moe.set_option("gemm_wave_rows", 2)
+        moe.set_option("small_tiles", 1)
+    return y, ysh, perm.cpu().numpy(), off.cpu().numpy(), li
+
+
+FFN_CASES = [
+    # name, overrides, skew, wave_rows, small_tiles, row_token
+    ("C1", {}, None, 2, 1, False),
+    ("C1", {}, None, 1, 1, True),
+    ("C1", dict(T=333, H=192, F=320), None, 2, 0, False),        # ragged rows, N not a multiple of the tile
+    ("C4", dict(T=512, H=256, F=192, E=16, top_k=4), None, 2, 1, True),   # shared experts, K-concatenated down proj
+    ("C4", dict(T=300, H=128, F=128, E=16, top_k=4), None, 1, 1, False),
+    ("C5", dict(T=700, H=256, F=128, E=40, top_k=3), "one", 2, 1, False),  # one hot expert, tiny and empty experts
+    ("C1", dict(T=40, H=64, F=64, E=4, top_k=1), None, 2, 1, False),
+]
+
+
+@pytest.mark.parametrize("name,over,skew,wave_rows,small_tiles,row_token", FFN_CASES)
+def test_grouped_ffn(moe, name, over, skew, wave_rows, small_tiles, row_token):
+    cfg = scaled_config(name, **over) if over else get_config(name)
+    say("grouped_ffn", cfg, skew, wave_rows, small_tiles, row_token)
+    rng = np.random.default_rng(cfg.T + cfg.E)
+    idx_h = random_routing(rng, cfg.T, cfg.E, cfg.top_k, skew)
+    y, ysh, perm, off, li = run_ffn_stage(moe, cfg, idx_h, wave_rows, small_tiles, row_token)
+    u = torch_bf16_to_u16
+    hw1 = [u(t) for t in li.w1]; hw3 = [u(t) for t in li.w3]; hw2 = [u(t) for t in li.w2]
+    hx = u(li.x)
+    rows_x = hx[perm // cfg.top_k]
+    eid = np.repeat(np.arange(cfg.E, dtype=np.int32), np.diff(off))
+    ref = orc.expert_rows(rows_x, eid, hw1, hw3, hw2)
+    rep = P.assert_output(y.float().cpu().numpy(), ref, "y_perm")
+    say(rep)
+    if cfg.num_shared:
+        ref_s = np.zeros((cfg.T, cfg.H), np.float32)
+        for s in range(cfg.num_shared):
+            ref_s += orc.expert_rows(hx, np.full(cfg.T, cfg.E + s, np.int32), hw1, hw3, hw2)
+        say(P.assert_output(ysh.float().cpu().numpy(), ref_s, "y_shared"))
+
+
+def test_grouped_ffn_single_expert_is_dense_mlp(moe):
+    """E = 1, top-1: the grouped FFN is a dense SwiGLU MLP; checked against torch fp64 on the CPU."""
+    cfg = scaled_config("C1", T=200, H=128, F=256, E=1, top_k=1)
+    idx_h = np.zeros((cfg.T, 1), np.int32)
+    y, _, perm, off, li = run_ffn_stage(moe, cfg, idx_h)
+    assert (perm == np.arange(cfg.T)).all()
+    x = li.x.double().cpu()
+    ref = (torch.nn.functional.silu(x @ li.w1[0].double().cpu()) * (x @ li.w3[0].double().cpu())) @ li.w2[0].double().cpu()
+    say(P.assert_output(y.float().cpu().numpy(), ref.numpy(), "dense"))
+
+
+def test_grouped_ffn_exact_scaling(moe):
+    """Doubling W2 doubles y bit-exactly (power-of-two scaling commutes with every rounding)."""
+    from paper_2503_09716_amd import shape_of
+    cfg = scaled_config("C1", T=128, H=128, F=128, E=4, top_k=2)
+    rng = np.random.default_rng(5)
+    idx_h = random_routing(rng, cfg.T, cfg.E, cfg.top_k)
+    y1, _, _, _, li = run_ffn_stage(moe, cfg, idx_h)
+    shape = shape_of(cfg)
+    w1p, w3p, w2p = moe.pack_experts(li.w1, li.w3, [w * 2 for w in li.w2])
+    R = cfg.T * cfg.top_k
+    idx = torch.from_numpy(idx_h).cuda()
+    x_perm = torch.empty((R, cfg.H), dtype=torch.bfloat16, device="cuda")
+    off = torch.empty(cfg.E + 1, dtype=torch.int32, device="cuda")
+    perm = torch.empty(R, dtype=torch.int32, device="cuda"); inv = torch.empty_like(perm)
+    ws = moe.new_workspace(shape)
+    moe.permute(shape, li.x, idx, x_perm, off, perm, inv, None, ws)
+    h = torch.empty((R, cfg.F), dtype=torch.bfloat16, device="cuda")
+    y2 = torch.empty((R, cfg.H), dtype=torch.bfloat16, device="cuda")
+    moe.grouped_ffn(shape, x_perm, None, None, off, w1p, w3p, w2p, h, y2, None, ws)
+    torch.cuda.synchronize()
+    assert torch.equal((y1.float() * 2), y2.float())
+
+
+COMBINE_CASES = [(256, 512, 2, False), (333, 2048, 6, True), (1, 64, 1, False), (100, 5120, 6, True)]
+
+
+@pytest.mark.parametrize("T,H,k,shared", COMBINE_CASES)
+def test_combine(moe, T, H, k, shared):
+    from paper_2503_09716_amd import make_shape
+    say("combine", T, H, k, shared)
+    rng = np.random.default_rng(T + H)
+    shape = make_shape(T, H, 64, max(k, 8), k, 1 if shared else 0, False)
+    y = normal_bf16(9, 0, (T * k, H), 1.0, "cuda")
+    ysh = normal_bf16(9, 1, (T, H), 1.0, "cuda") if shared else None
+    inv_h = rng.permutation(T * k).astype(np.int32)
+    w_h = rng.random((T, k)).astype(np.float32)
+    out = torch.empty((T, H), dtype=torch.bfloat16, device="cuda")
+    moe.combine(shape, y, torch.from_numpy(inv_h).cuda(), torch.from_numpy(w_h).cuda(), ysh, out)
+    torch.cuda.synchronize()
+    ref = orc.combine(torch_bf16_to_u16(y), inv_h, w_h, None if ysh is None else torch_bf16_to_u16(ysh))
+    got = out.float().cpu().numpy()
+    # one bf16 rounding of an fp32 sum: half an ulp of bf16 (2^-9 relative) plus fp32 noise
+    assert (np.abs(got - ref) <= np.abs(ref) * 2.0 ** -8 + 1e-6).all()
+    # k = 1, w = 1 is a pure gather: bit-exact
+    inv1 = rng.permutation(T).astype(np.int32)
+    shape1 = make_shape(T, H, 64, 8, 1, 0, False)
+    out1 = torch.empty((T, H), dtype=torch.bfloat16, device="cuda")
+    moe.combine(shape1, y[:T].contiguous(), torch.from_numpy(inv1).cuda(), torch.ones((T, 1), device="cuda"), None, out1)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(torch_bf16_to_u16(out1), torch_bf16_to_u16(y[:T])[inv1])
+
+
+def test_pack_weight_is_a_transpose(moe):
+    w = normal_bf16(4, 0, (192, 1000), 0.02, "cuda")
+    p = moe.pack_weight(w)
+    torch.cuda.synchronize()
+    assert torch.equal(p, w.t().contiguous())
+
+
+def test_error_paths(moe):
+    """Argument errors are reported before anything is enqueued."""
+    from paper_2503_09716_amd import MoeError, make_shape
+    shape = make_shape(64, 64, 64, 4, 2)
+    x = torch.zeros((64, 64), dtype=torch.bfloat16, device="cuda")
+    idx = torch.zeros((64, 2), dtype=torch.int32, device="cuda")
+    w = torch.zeros((64, 2), dtype=torch.float32, device="cuda")
+    with pytest.raises(MoeError) as e:
+        moe.route(shape, None, x, None, idx, w)
+    assert e.value.status == 1
+    with pytest.raises(MoeError) as e:
+        moe.route(make_shape(64, 60, 64, 4, 2), x, x, None, idx, w)
+    assert e.value.status == 2
+    ws = torch.empty(1024, dtype=torch.uint8, device="cuda")
+    off = torch.zeros(5, dtype=torch.int32, device="cuda")
+    perm = torch.zeros(128, dtype=torch.int32, device="cuda")
+    with pytest.raises(MoeError) as e:
+        moe.permute(shape, x, idx, None, off, perm, perm.clone(), None, ws)
+    assert e.value.status == 3 and "workspace" in str(e.value)
+    with pytest.raises(MoeError):
+        moe.set_option("no_such_option", 1)
+    with pytest.raises(MoeError):
+        moe.set_option("gemm_wave_rows", 3)
+    torch.cuda.synchronize()
