@@ -90,7 +90,12 @@ size_t moe_workspace_bytes(const moe_shape* shape);
  *   "gemm_wave_rows"  1 | 2   wave grid of the GEMM workgroup is (rows x 4/rows)
  *   "gemm_group_m"    1..64   m-tiles swept together along n (L2 reuse of weight panels)
  *   "xcd_remap"       0 | 1   give each XCD runs of consecutive tiles
- *   "small_tiles"     0 | 1   use 128/64/32-row tiles for the ragged tail of an expert */
+ *   "small_tiles"     0 | 1   use 128/64/32-row tiles for the ragged tail of an expert
+ *   "y_fp32"          0 | 1   dtype of y_perm / y_shared: 1 (default) fp32, 0 bf16.  bf16 halves the
+ *                             traffic of the down projection's store and of the combine's loads, but
+ *                             rounds each expert output to 8 mantissa bits before the weighted sum
+ *   "out_fp32"        0 | 1   dtype of the layer output written by moe_combine / moe_layer:
+ *                             0 (default) bf16 = round-to-nearest-even of the fp32 sum, 1 fp32 */
 moe_status moe_set_option(moe_ctx* ctx, const char* key, int32_t value);
 
 /* One-time weight packing: w_logical [rows, cols] bf16 (device) -> w_packed [cols, rows]
@@ -125,8 +130,8 @@ moe_status moe_permute(moe_ctx* ctx, const moe_shape* shape, const void* x_bf16,
 
 /* Per-expert SwiGLU FFN over the grouped rows (Sec. 2 "each token is processed by k selected
  * experts"; experts with no rows are skipped), as two grouped bf16 GEMMs with fp32
- * accumulation: h = silu(X_e W1_e) * (X_e W3_e) rounded to bf16, then y = h W2_e rounded
- * to bf16.  Shared experts E..E+num_shared-1 run on all T tokens of x; their outputs are
+ * accumulation: h = silu(X_e W1_e) * (X_e W3_e) rounded to bf16, then y = h W2_e kept in
+ * fp32 (or rounded to bf16 under option "y_fp32" = 0).  Shared experts E..E+num_shared-1 run on all T tokens of x; their outputs are
  * summed (one GEMM over the concatenated contraction dimension) into y_shared.
  *   x_perm_bf16 [T*k,H] device in; ignored (may be NULL) when row_token is given
  *   row_token_or_null [T*k] int32 device: row r of the expert input is x[row_token[r],:]
@@ -134,29 +139,32 @@ moe_status moe_permute(moe_ctx* ctx, const moe_shape* shape, const void* x_bf16,
  *   expert_offsets [E+1] int32 device in
  *   w1p, w3p, w2p: host arrays of E+num_shared device pointers, packed layout (see above)
  *   h_scratch_bf16 [(T*k + T*num_shared), F] device scratch
- *   y_perm_bf16 [T*k,H] device out; y_shared_bf16 [T,H] device out (NULL iff num_shared == 0)
+ *   y_perm [T*k,H] device out; y_shared [T,H] device out (NULL iff num_shared == 0); both fp32,
+ *   or bf16 under option "y_fp32" = 0
  *   workspace: device, at least moe_workspace_bytes(shape). */
 moe_status moe_grouped_ffn(moe_ctx* ctx, const moe_shape* shape, const void* x_perm_bf16,
                            const int32_t* row_token_or_null, const void* x_bf16,
                            const int32_t* expert_offsets, const void* const* w1p, const void* const* w3p,
-                           const void* const* w2p, void* h_scratch_bf16, void* y_perm_bf16,
-                           void* y_shared_bf16, void* workspace, size_t workspace_bytes, void* hip_stream);
+                           const void* const* w2p, void* h_scratch_bf16, void* y_perm, void* y_shared,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Weighted sum back in token order (Sec. 2 "weighted average of the outputs from these
  * experts", plus the shared expert all tokens pass through):
  *   out[t,:] = sum_{j<k} topk_w[t,j] * y_perm[inv_perm[t*k+j],:] (+ y_shared[t,:]),
  * fp32 accumulation in the order j = 0..k-1 then shared, one store per element, no atomics.
- *   y_perm_bf16 [T*k,H], inv_perm [T*k], topk_w [T,k] fp32 (already carries routed_scale),
- *   y_shared_or_null [T,H] bf16, out_bf16 [T,H]: all device. */
-moe_status moe_combine(moe_ctx* ctx, const moe_shape* shape, const void* y_perm_bf16, const int32_t* inv_perm,
-                       const float* topk_w, const void* y_shared_or_null, void* out_bf16, void* hip_stream);
+ *   y_perm [T*k,H] and y_shared_or_null [T,H]: fp32 (bf16 under "y_fp32" = 0); inv_perm [T*k];
+ *   topk_w [T,k] fp32 (already carries routed_scale); out [T,H] bf16 (fp32 under "out_fp32" = 1):
+ *   all device. */
+moe_status moe_combine(moe_ctx* ctx, const moe_shape* shape, const void* y_perm, const int32_t* inv_perm,
+                       const float* topk_w, const void* y_shared_or_null, void* out, void* hip_stream);
 
 /* The whole expert module on one stream: route -> permute (indices only; the row gather is
  * fused into the first GEMM's loads) -> grouped FFN -> combine.  Same results as the staged
- * calls bit for bit.  All intermediates live in `workspace`. */
+ * calls bit for bit.  All intermediates live in `workspace`.  out [T,H] is bf16, or fp32
+ * under option "out_fp32" = 1. */
 moe_status moe_layer(moe_ctx* ctx, const moe_shape* shape, const void* x_bf16, const void* wg_bf16,
                      const float* gate_bias, const void* const* w1p, const void* const* w3p,
-                     const void* const* w2p, void* out_bf16, void* workspace, size_t workspace_bytes,
+                     const void* const* w2p, void* out, void* workspace, size_t workspace_bytes,
                      void* hip_stream);
 
 /* Device pointers into a workspace last used by moe_layer with this shape, for inspection:

@@ -211,22 +211,27 @@ void oracle_layer(const uint16_t* x, const int32_t* tokens, int ntok,
 
 /* Weighted combine on its own (Sec. 2 "weighted average of the outputs from these
  * experts"): out[t,:] = sum_j w[t,j] * y_perm[inv_perm[t*k+j],:] (+ y_shared[t,:]).
- * y_perm [R,H] and y_shared [T,H] are bf16 bits (the stage's input dtype); products and
- * sums in fp32 in rank order, shared added last.  out [T,H] fp32. */
-void oracle_combine(const uint16_t* y_perm, const int32_t* inv_perm, const float* w,
-                    const uint16_t* y_shared, int T, int H, int k, float* out)
+ * y_perm [R,H] and y_shared [T,H] are the stage's inputs, fp32 when y_is_f32 else bf16 bits;
+ * products and sums in fp32 in rank order, shared added last.  out [T,H] fp32. */
+static inline float y_at(const void* y, int y_is_f32, size_t i)
+{
+    return y_is_f32 ? ((const float*)y)[i] : bf16_to_f32(((const uint16_t*)y)[i]);
+}
+
+void oracle_combine(const void* y_perm, int y_is_f32, const int32_t* inv_perm, const float* w,
+                    const void* y_shared, int T, int H, int k, float* out)
 {
 #pragma omp parallel for schedule(static)
     for (int t = 0; t < T; ++t) {
         float* o = out + (size_t)t * H;
         for (int h = 0; h < H; ++h) o[h] = 0.0f;
         for (int j = 0; j < k; ++j) {
-            const uint16_t* yr = y_perm + (size_t)inv_perm[(size_t)t * k + j] * H;
+            const size_t r = (size_t)inv_perm[(size_t)t * k + j];
             const float wj = w[(size_t)t * k + j];
-            for (int h = 0; h < H; ++h) o[h] += wj * bf16_to_f32(yr[h]);
+            for (int h = 0; h < H; ++h) o[h] += wj * y_at(y_perm, y_is_f32, r * H + h);
         }
         if (y_shared)
-            for (int h = 0; h < H; ++h) o[h] += bf16_to_f32(y_shared[(size_t)t * H + h]);
+            for (int h = 0; h < H; ++h) o[h] += y_at(y_shared, y_is_f32, (size_t)t * H + h);
     }
 }
 

@@ -134,17 +134,24 @@ def layer(x, idx, w, w1, w3, w2, E: int, num_shared: int, tokens=None):
 
 
 def combine(y_perm, inv_perm, w, y_shared=None):
-    """out[t] = sum_j w[t,j] * y_perm[inv_perm[t*k+j]] (+ y_shared[t]); float32 [T,H]."""
-    y_perm = _u16(y_perm)
+    """out[t] = sum_j w[t,j] * y_perm[inv_perm[t*k+j]] (+ y_shared[t]); float32 [T,H].
+    y_perm / y_shared: float32 arrays, or uint16 arrays of bf16 bit patterns."""
+    y_perm = np.ascontiguousarray(y_perm)
+    f32 = y_perm.dtype == np.float32
+    assert f32 or y_perm.dtype == np.uint16
     R, H = y_perm.shape
     w = np.ascontiguousarray(w, dtype=np.float32)
     T, k = w.shape
     assert R == T * k
     inv = np.ascontiguousarray(inv_perm, dtype=np.int32).reshape(-1)
     assert len(inv) == R and inv.min(initial=0) >= 0 and inv.max(initial=0) < R
-    ys = None if y_shared is None else _u16(y_shared)
+    ys = None
+    if y_shared is not None:
+        ys = np.ascontiguousarray(y_shared)
+        assert ys.dtype == y_perm.dtype and ys.shape == (T, H)
     out = np.empty((T, H), np.float32)
-    lib().oracle_combine(_p(y_perm, _u16p), _p(inv, _i32p), _p(w, _f32p), _p(ys, _u16p),
+    lib().oracle_combine(C.c_void_p(y_perm.ctypes.data), C.c_int(1 if f32 else 0), _p(inv, _i32p), _p(w, _f32p),
+                         None if ys is None else C.c_void_p(ys.ctypes.data),
                          C.c_int(T), C.c_int(H), C.c_int(k), _p(out, _f32p))
     return out
 

@@ -27,6 +27,8 @@ struct moe_ctx {
     int device = 0;
     char err[512] = {0};
     GemmConfig gemm{2, 8, 1, 1};
+    bool y_fp32 = true;    // dtype of y_perm / y_shared
+    bool out_fp32 = false; // dtype of the layer output
     // Ring of device pointer tables [3][MAX_GROUPS] (W1p, W3p, W2p), each with a pinned host
     // staging copy and an event marking the end of its upload.
     void** d_tab[TABLE_SLOTS] = {nullptr};
@@ -102,8 +104,8 @@ Layout make_layout(const moe_shape& s) {
     L.plan = take(sizeof(PlanHeader));
     L.descs = take((size_t)max_mtiles(s) * sizeof(TileDesc));
     L.h = take((R + Rs) * s.F * 2);
-    L.y_perm = take(R * s.H * 2);
-    L.y_shared = take(Rs ? (size_t)s.T * s.H * 2 : 0);
+    L.y_perm = take(R * s.H * 4);  // sized for fp32 y
+    L.y_shared = take(Rs ? (size_t)s.T * s.H * 4 : 0);
     L.total = o;
     return L;
 }
@@ -201,6 +203,7 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     a.group_m = c->gemm.group_m;
     a.xcd_remap = c->gemm.xcd_remap;
     a.small_tiles = c->gemm.small_tiles;
+    a.out_fp32 = 0;
     // GEMM 1: [rows, H] x W1p/W3p [F, H] -> h [rows, F]
     a.a_routed = (const char*)(row_token ? x : x_perm);
     a.a_shared = (const char*)x;
@@ -228,6 +231,7 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     a.K = s.F;
     a.N = s.H;
     a.nseg_shared = s.num_shared > 0 ? s.num_shared : 1;
+    a.out_fp32 = c->y_fp32 ? 1 : 0;
     a.n_tiles = (s.H + 255) / 256;
     {
         StageTimer tm(c, st, MOE_STAGE_FFN_DOWN);
@@ -287,6 +291,8 @@ moe_status moe_set_option(moe_ctx* c, const char* key, int32_t v) {
     if (!strcmp(key, "gemm_group_m") && v >= 1 && v <= 64) { c->gemm.group_m = v; return MOE_OK; }
     if (!strcmp(key, "xcd_remap") && (v == 0 || v == 1)) { c->gemm.xcd_remap = v; return MOE_OK; }
     if (!strcmp(key, "small_tiles") && (v == 0 || v == 1)) { c->gemm.small_tiles = v; return MOE_OK; }
+    if (!strcmp(key, "y_fp32") && (v == 0 || v == 1)) { c->y_fp32 = v != 0; return MOE_OK; }
+    if (!strcmp(key, "out_fp32") && (v == 0 || v == 1)) { c->out_fp32 = v != 0; return MOE_OK; }
     return fail(c, MOE_E_ARG, "unknown option or value out of range: %s=%d", key, (int)v);
 }
 
@@ -354,7 +360,7 @@ moe_status moe_combine(moe_ctx* c, const moe_shape* s, const void* y_perm, const
     if (!y_perm || !inv_perm || !w || !out) return fail(c, MOE_E_ARG, "combine: NULL pointer");
     hipStream_t hs = (hipStream_t)stream;
     StageTimer tm(c, hs, MOE_STAGE_COMBINE);
-    HIP_TRY(c, launch_combine(*s, y_perm, inv_perm, w, y_shared, out, hs));
+    HIP_TRY(c, launch_combine(*s, y_perm, inv_perm, w, y_shared, out, c->y_fp32, c->out_fp32, hs));
     return MOE_OK;
 }
 
@@ -388,7 +394,7 @@ moe_status moe_layer(moe_ctx* c, const moe_shape* s, const void* x, const void* 
         return st;
     {
         StageTimer tm(c, hs, MOE_STAGE_COMBINE);
-        HIP_TRY(c, launch_combine(*s, w8 + L.y_perm, inv_perm, tw, y_shared, out, hs));
+        HIP_TRY(c, launch_combine(*s, w8 + L.y_perm, inv_perm, tw, y_shared, out, c->y_fp32, c->out_fp32, hs));
     }
     return MOE_OK;
 }

@@ -11,34 +11,52 @@
 namespace moe {
 namespace {
 
-__device__ __forceinline__ void accum8(float (&acc)[8], const uint4 v, const float w) {
-    const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+// acc += w * (8 consecutive elements of a row, starting at element 8*c)
+template <bool F32>
+__device__ __forceinline__ void accum8(float (&acc)[8], const void* __restrict__ row, const int c, const float w) {
+    if (F32) {
+        const float4* p = reinterpret_cast<const float4*>(row) + 2 * c;
+        const float4 a = p[0], b = p[1];
+        const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        acc[2 * q] = fmaf(w, __uint_as_float(u[q] << 16), acc[2 * q]);
-        acc[2 * q + 1] = fmaf(w, __uint_as_float(u[q] & 0xffff0000u), acc[2 * q + 1]);
+        for (int i = 0; i < 8; ++i) acc[i] = fmaf(w, v[i], acc[i]);
+    } else {
+        const uint4 v = reinterpret_cast<const uint4*>(row)[c];
+        const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            acc[2 * q] = fmaf(w, __uint_as_float(u[q] << 16), acc[2 * q]);
+            acc[2 * q + 1] = fmaf(w, __uint_as_float(u[q] & 0xffff0000u), acc[2 * q + 1]);
+        }
     }
 }
 
-__global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ y_perm, const int32_t* __restrict__ inv_perm,
-                                                      const float* __restrict__ w, const uint4* __restrict__ y_shared,
-                                                      int T, int k, int row16, uint4* __restrict__ out) {
+template <bool YF32, bool OF32>
+__global__ __launch_bounds__(256) void combine_kernel(const char* __restrict__ y_perm, const int32_t* __restrict__ inv_perm,
+                                                      const float* __restrict__ w, const char* __restrict__ y_shared,
+                                                      int k, int H, char* __restrict__ out) {
     const int t = blockIdx.x;
-    (void)T;
-    for (int c = threadIdx.x; c < row16; c += 256) {
+    const size_t ybytes = (size_t)H * (YF32 ? 4 : 2);
+    for (int c = threadIdx.x; c < H / 8; c += 256) {
         float acc[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i] = 0.f;
         for (int j = 0; j < k; ++j) {
             const int r = inv_perm[(size_t)t * k + j];
             const float wj = w[(size_t)t * k + j];
-            accum8(acc, y_perm[(size_t)r * row16 + c], wj);
+            accum8<YF32>(acc, y_perm + (size_t)r * ybytes, c, wj);
         }
-        if (y_shared) accum8(acc, y_shared[(size_t)t * row16 + c], 1.0f);
-        bf16x8 o;
+        if (y_shared) accum8<YF32>(acc, y_shared + (size_t)t * ybytes, c, 1.0f);
+        if (OF32) {
+            float4* o = reinterpret_cast<float4*>(out + (size_t)t * H * 4) + 2 * c;
+            o[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+            o[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+        } else {
+            bf16x8 o;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) o[i] = (__bf16)acc[i];
-        out[(size_t)t * row16 + c] = *reinterpret_cast<uint4*>(&o);
+            for (int i = 0; i < 8; ++i) o[i] = (__bf16)acc[i];
+            reinterpret_cast<bf16x8*>(out + (size_t)t * H * 2)[c] = o;
+        }
     }
 }
 
@@ -62,9 +80,15 @@ __global__ __launch_bounds__(256) void transpose_kernel(const uint16_t* __restri
 }  // namespace
 
 hipError_t launch_combine(const moe_shape& s, const void* y_perm, const int32_t* inv_perm, const float* w,
-                          const void* y_shared, void* out, hipStream_t st) {
-    hipLaunchKernelGGL(combine_kernel, dim3(s.T), dim3(256), 0, st, (const uint4*)y_perm, inv_perm, w,
-                       (const uint4*)y_shared, s.T, s.top_k, s.H / 8, (uint4*)out);
+                          const void* y_shared, void* out, bool y_fp32, bool out_fp32, hipStream_t st) {
+#define COMBINE(Y, O)                                                                                           \
+    hipLaunchKernelGGL((combine_kernel<Y, O>), dim3(s.T), dim3(256), 0, st, (const char*)y_perm, inv_perm, w,   \
+                       (const char*)y_shared, s.top_k, s.H, (char*)out)
+    if (y_fp32 && out_fp32) COMBINE(true, true);
+    else if (y_fp32) COMBINE(true, false);
+    else if (out_fp32) COMBINE(false, true);
+    else COMBINE(false, false);
+#undef COMBINE
     return hipGetLastError();
 }
 

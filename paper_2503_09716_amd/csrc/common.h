@@ -48,6 +48,7 @@ struct GemmArgs {
     int32_t group_m;
     int32_t xcd_remap;
     int32_t small_tiles;       // 1: a short tail tile runs the 128/64/32-row variant
+    int32_t out_fp32;          // GEMM2: 1 = y stored as fp32, 0 = bf16 (GEMM1 always stores bf16)
 };
 
 struct GemmConfig {
@@ -80,7 +81,7 @@ hipError_t launch_ffn_gemm(bool gated, const GemmArgs& a, const GemmConfig& cfg,
 hipError_t ffn_gemm_init();  // one-time function attributes (dynamic LDS size)
 
 hipError_t launch_combine(const moe_shape& s, const void* y_perm, const int32_t* inv_perm, const float* w,
-                          const void* y_shared, void* out, hipStream_t st);
+                          const void* y_shared, void* out, bool y_fp32, bool out_fp32, hipStream_t st);
 hipError_t launch_transpose(const void* in, int rows, int cols, void* out, hipStream_t st);
 
 }  // namespace moe

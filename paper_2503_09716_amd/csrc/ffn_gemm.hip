@@ -254,6 +254,20 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
                 *reinterpret_cast<bf16x8*>(orow + (size_t)col * 2) = o0;
                 *reinterpret_cast<bf16x8*>(orow + (size_t)col * 2 + 16) = o1;
             }
+        } else if (p.out_fp32) {
+            orow = out + (size_t)(orow_base + r) * (size_t)N * 4;
+#pragma unroll
+            for (int j = 0; j < TJ; ++j) {
+                const int col = n0 + (bw0 + j) * 32 + g * 16;
+                if (col >= N) continue;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    f32x4 o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = acc[j][i][q * 4 + e];
+                    *reinterpret_cast<f32x4*>(orow + (size_t)col * 4 + q * 16) = o;
+                }
+            }
         } else {
 #pragma unroll
             for (int j = 0; j < TJ; ++j) {

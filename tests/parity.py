@@ -3,7 +3,10 @@ oracle on the same bytes, compare to the stated bars.
 
 Bars:  routing indices and the permutation bit-exact, except at reported top-k near-ties
 (oracle logit margin < 1e-5); routing weights to 1e-5 relative; FFN / layer output
-max-abs error <= 2e-2 x RMS(oracle output)."""
+max-abs error <= 2e-2 x RMS(oracle output), asserted on the fp32 form of the result.  A bf16
+result must be the round-to-nearest-even of that fp32 result bit for bit; against the oracle
+it is held to the same bar widened by the rounding it cannot avoid (half a bf16 ulp = up to
+2^-8 |value|, which alone is 1.7e-2..2.2e-2 x RMS for an element 4.3..5.7 sigma out)."""
 from __future__ import annotations
 
 import numpy as np
@@ -78,6 +81,17 @@ def assert_output(out_gpu: np.ndarray, out_ref: np.ndarray, what: str = "output"
     return rep
 
 
+def assert_output_bf16(out_gpu: np.ndarray, out_ref: np.ndarray, what: str = "output"):
+    """Per-element bound for a result stored in bf16: kernel error bar/2 plus half a bf16 ulp."""
+    ref = out_ref.astype(np.float64)
+    rms = float(np.sqrt((ref ** 2).mean()))
+    err = np.abs(out_gpu.astype(np.float64) - ref)
+    bound = 0.5 * OUT_BAR * rms + np.abs(ref) * 2.0 ** -8
+    worst = float((err / bound).max())
+    assert worst <= 1.0, "%s: bf16 result off by %.3f x its bound" % (what, worst)
+    return output_report(out_gpu, out_ref)
+
+
 class GpuLayer:
     """One synthetic layer resident on the GPU with packed weights, plus host copies for the oracle."""
 
@@ -97,13 +111,25 @@ class GpuLayer:
             self.hw3 = [host_u16(w) for w in li.w3]
             self.hw2 = [host_u16(w) for w in li.w2]
 
-    def run_layer(self):
+    def run_layer(self, out_fp32: bool = False):
         cfg = self.cfg
-        out = torch.empty((cfg.T, cfg.H), dtype=torch.bfloat16, device="cuda")
-        self.moe.layer(self.shape, self.x, self.wg, self.bias, self.w1p, self.w3p, self.w2p, out, self.ws,
-                       tables=self.tables)
-        torch.cuda.synchronize()
+        out = torch.empty((cfg.T, cfg.H), dtype=torch.float32 if out_fp32 else torch.bfloat16, device="cuda")
+        self.moe.set_option("out_fp32", 1 if out_fp32 else 0)
+        try:
+            self.moe.layer(self.shape, self.x, self.wg, self.bias, self.w1p, self.w3p, self.w2p, out, self.ws,
+                           tables=self.tables)
+            torch.cuda.synchronize()
+        finally:
+            self.moe.set_option("out_fp32", 0)
         return out
+
+    def run_layer_both(self):
+        """fp32 output (held to the bar) and bf16 output (must be its exact RNE rounding)."""
+        o32 = self.run_layer(True)
+        o16 = self.run_layer(False)
+        assert torch.equal(o32.to(torch.bfloat16).view(torch.int16), o16.view(torch.int16)), \
+            "bf16 output is not the round-to-nearest-even of the fp32 output"
+        return o32, o16
 
     def oracle_route(self, tokens=None):
         cfg = self.cfg
@@ -115,7 +141,8 @@ class GpuLayer:
         return orc.layer(self.hx, idx, w, self.hw1, self.hw3, self.hw2, cfg.E, cfg.num_shared, tokens=tokens)
 
 
-def check_layer_against_oracle(gl: GpuLayer, out: torch.Tensor, tokens=None, check_all_routing: bool = True):
+def check_layer_against_oracle(gl: GpuLayer, out: torch.Tensor, tokens=None, check_all_routing: bool = True,
+                               out16: torch.Tensor = None):
     """Full check of one moe_layer result.  tokens=None: every token through the oracle;
     otherwise the FFN/combine part only for the listed tokens (routing still for all tokens
     when check_all_routing)."""
@@ -145,6 +172,9 @@ def check_layer_against_oracle(gl: GpuLayer, out: torch.Tensor, tokens=None, che
     out_ref = gl.oracle_layer(idx[tokens], w[tokens], tokens=tokens)
     out_gpu = out[torch.from_numpy(tokens.astype(np.int64)).cuda()].float().cpu().numpy()
     report["output"] = assert_output(out_gpu, out_ref, "layer output (%s)" % cfg.name)
+    if out16 is not None:
+        got16 = out16[torch.from_numpy(tokens.astype(np.int64)).cuda()].float().cpu().numpy()
+        report["output_bf16"] = assert_output_bf16(got16, out_ref, "bf16 layer output (%s)" % cfg.name)
     return report
 
 

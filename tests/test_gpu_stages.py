@@ -127,7 +127,7 @@ def test_permute(moe, T, E, k, skew):
     np.testing.assert_array_equal(np.bincount(perm.cpu().numpy() // k, minlength=T), np.full(T, k))
 
 
-def run_ffn_stage(moe, cfg, idx_h, wave_rows=2, small_tiles=1, use_row_token=False):
+def run_ffn_stage(moe, cfg, idx_h, wave_rows=2, small_tiles=1, use_row_token=False, y_fp32=True):
     """Runs moe_permute + moe_grouped_ffn for a given routing; returns (y_perm, y_shared, perm, li)."""
     from paper_2503_09716_amd import shape_of
     shape = shape_of(cfg)
@@ -143,10 +143,12 @@ def run_ffn_stage(moe, cfg, idx_h, wave_rows=2, small_tiles=1, use_row_token=Fal
     ws = moe.new_workspace(shape)
     moe.permute(shape, li.x, idx, x_perm, off, perm, inv, rtok, ws)
     h = torch.empty((R + cfg.T * cfg.num_shared, cfg.F), dtype=torch.bfloat16, device="cuda")
-    y = torch.full((R, cfg.H), float("nan"), dtype=torch.bfloat16, device="cuda")
-    ysh = torch.full((cfg.T, cfg.H), float("nan"), dtype=torch.bfloat16, device="cuda") if cfg.num_shared else None
+    ydt = torch.float32 if y_fp32 else torch.bfloat16
+    y = torch.full((R, cfg.H), float("nan"), dtype=ydt, device="cuda")
+    ysh = torch.full((cfg.T, cfg.H), float("nan"), dtype=ydt, device="cuda") if cfg.num_shared else None
     moe.set_option("gemm_wave_rows", wave_rows)
     moe.set_option("small_tiles", small_tiles)
+    moe.set_option("y_fp32", 1 if y_fp32 else 0)
     try:
         moe.grouped_ffn(shape, None if use_row_token else x_perm, rtok if use_row_token else None, li.x, off,
                         w1p, w3p, w2p, h, y, ysh, ws)
@@ -154,6 +156,7 @@ def run_ffn_stage(moe, cfg, idx_h, wave_rows=2, small_tiles=1, use_row_token=Fal
     finally:
         moe.set_option("gemm_wave_rows", 2)
         moe.set_option("small_tiles", 1)
+        moe.set_option("y_fp32", 1)
     return y, ysh, perm.cpu().numpy(), off.cpu().numpy(), li
 
 
@@ -191,6 +194,17 @@ def test_grouped_ffn(moe, name, over, skew, wave_rows, small_tiles, row_token):
         say(P.assert_output(ysh.float().cpu().numpy(), ref_s, "y_shared"))
 
 
+def test_grouped_ffn_bf16_y(moe):
+    """Option y_fp32 = 0: y in bf16 is the RNE rounding of the fp32 y, bit for bit."""
+    cfg = scaled_config("C4", T=300, H=256, F=192, E=16, top_k=4)
+    rng = np.random.default_rng(3)
+    idx_h = random_routing(rng, cfg.T, cfg.E, cfg.top_k)
+    y32, s32, _, _, _ = run_ffn_stage(moe, cfg, idx_h)
+    y16, s16, _, _, _ = run_ffn_stage(moe, cfg, idx_h, y_fp32=False)
+    assert torch.equal(y32.to(torch.bfloat16).view(torch.int16), y16.view(torch.int16))
+    assert torch.equal(s32.to(torch.bfloat16).view(torch.int16), s16.view(torch.int16))
+
+
 def test_grouped_ffn_single_expert_is_dense_mlp(moe):
     """E = 1, top-1: the grouped FFN is a dense SwiGLU MLP; checked against torch fp64 on the CPU."""
     cfg = scaled_config("C1", T=200, H=128, F=256, E=1, top_k=1)
@@ -219,39 +233,56 @@ def test_grouped_ffn_exact_scaling(moe):
     ws = moe.new_workspace(shape)
     moe.permute(shape, li.x, idx, x_perm, off, perm, inv, None, ws)
     h = torch.empty((R, cfg.F), dtype=torch.bfloat16, device="cuda")
-    y2 = torch.empty((R, cfg.H), dtype=torch.bfloat16, device="cuda")
+    y2 = torch.empty((R, cfg.H), dtype=torch.float32, device="cuda")
     moe.grouped_ffn(shape, x_perm, None, None, off, w1p, w3p, w2p, h, y2, None, ws)
     torch.cuda.synchronize()
-    assert torch.equal((y1.float() * 2), y2.float())
+    assert torch.equal(y1 * 2, y2)
 
 
-COMBINE_CASES = [(256, 512, 2, False), (333, 2048, 6, True), (1, 64, 1, False), (100, 5120, 6, True)]
+COMBINE_CASES = [(256, 512, 2, False, True), (333, 2048, 6, True, True), (1, 64, 1, False, True),
+                 (100, 5120, 6, True, False), (77, 1024, 2, False, False)]
 
 
-@pytest.mark.parametrize("T,H,k,shared", COMBINE_CASES)
-def test_combine(moe, T, H, k, shared):
+@pytest.mark.parametrize("T,H,k,shared,y_fp32", COMBINE_CASES)
+def test_combine(moe, T, H, k, shared, y_fp32):
     from paper_2503_09716_amd import make_shape
-    say("combine", T, H, k, shared)
+    say("combine", T, H, k, shared, y_fp32)
     rng = np.random.default_rng(T + H)
     shape = make_shape(T, H, 64, max(k, 8), k, 1 if shared else 0, False)
     y = normal_bf16(9, 0, (T * k, H), 1.0, "cuda")
     ysh = normal_bf16(9, 1, (T, H), 1.0, "cuda") if shared else None
+    if y_fp32:   # fp32 values with a full mantissa
+        y = y.float() * 1.0009765625
+        ysh = None if ysh is None else ysh.float() * 0.9990234375
+    to_host = (lambda t: t.cpu().numpy()) if y_fp32 else torch_bf16_to_u16
     inv_h = rng.permutation(T * k).astype(np.int32)
     w_h = rng.random((T, k)).astype(np.float32)
-    out = torch.empty((T, H), dtype=torch.bfloat16, device="cuda")
-    moe.combine(shape, y, torch.from_numpy(inv_h).cuda(), torch.from_numpy(w_h).cuda(), ysh, out)
-    torch.cuda.synchronize()
-    ref = orc.combine(torch_bf16_to_u16(y), inv_h, w_h, None if ysh is None else torch_bf16_to_u16(ysh))
-    got = out.float().cpu().numpy()
-    # one bf16 rounding of an fp32 sum: half an ulp of bf16 (2^-9 relative) plus fp32 noise
-    assert (np.abs(got - ref) <= np.abs(ref) * 2.0 ** -8 + 1e-6).all()
-    # k = 1, w = 1 is a pure gather: bit-exact
-    inv1 = rng.permutation(T).astype(np.int32)
-    shape1 = make_shape(T, H, 64, 8, 1, 0, False)
-    out1 = torch.empty((T, H), dtype=torch.bfloat16, device="cuda")
-    moe.combine(shape1, y[:T].contiguous(), torch.from_numpy(inv1).cuda(), torch.ones((T, 1), device="cuda"), None, out1)
-    torch.cuda.synchronize()
-    np.testing.assert_array_equal(torch_bf16_to_u16(out1), torch_bf16_to_u16(y[:T])[inv1])
+    inv = torch.from_numpy(inv_h).cuda(); w = torch.from_numpy(w_h).cuda()
+    ref = orc.combine(to_host(y), inv_h, w_h, None if ysh is None else to_host(ysh))
+    moe.set_option("y_fp32", 1 if y_fp32 else 0)
+    try:
+        out32 = torch.empty((T, H), dtype=torch.float32, device="cuda")
+        moe.set_option("out_fp32", 1)
+        moe.combine(shape, y, inv, w, ysh, out32)
+        moe.set_option("out_fp32", 0)
+        out16 = torch.empty((T, H), dtype=torch.bfloat16, device="cuda")
+        moe.combine(shape, y, inv, w, ysh, out16)
+        torch.cuda.synchronize()
+        # fp32 sums in the same order; the GPU fuses each multiply-add (one rounding instead of two)
+        np.testing.assert_allclose(out32.cpu().numpy(), ref, rtol=2e-6, atol=2e-6)
+        assert torch.equal(out32.to(torch.bfloat16).view(torch.int16), out16.view(torch.int16))
+        # k = 1, w = 1 is a pure gather: bit-exact
+        inv1 = rng.permutation(T).astype(np.int32)
+        shape1 = make_shape(T, H, 64, 8, 1, 0, False)
+        y1 = y[:T].contiguous()
+        moe.set_option("out_fp32", 1 if y_fp32 else 0)
+        out1 = torch.empty((T, H), dtype=y.dtype, device="cuda")
+        moe.combine(shape1, y1, torch.from_numpy(inv1).cuda(), torch.ones((T, 1), device="cuda"), None, out1)
+        torch.cuda.synchronize()
+        assert torch.equal(out1, y1[torch.from_numpy(inv1.astype(np.int64)).cuda()])
+    finally:
+        moe.set_option("y_fp32", 1)
+        moe.set_option("out_fp32", 0)
 
 
 def test_pack_weight_is_a_transpose(moe):
