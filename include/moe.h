@@ -87,10 +87,14 @@ const char* moe_last_error(const moe_ctx* ctx);
 size_t moe_workspace_bytes(const moe_shape* shape);
 
 /* Tuning knobs (host call).  Unknown key or out-of-range value: MOE_E_ARG.
- *   "gemm_wave_rows"  1 | 2   wave grid of the GEMM workgroup is (rows x 4/rows)
+ *   "gemm_waves"      4 | 8   wavefronts per GEMM workgroup (one or two per SIMD)
+ *   "gemm_wave_rows"  1|2|4   rows of the wave grid (rows x waves/rows): 1 or 2 with 4 waves (4 rows
+ *                             is treated as 2), 2 or 4 with 8 waves (1 row is treated as 2)
  *   "gemm_group_m"    1..64   m-tiles swept together along n (L2 reuse of weight panels)
  *   "xcd_remap"       0 | 1   give each XCD runs of consecutive tiles
  *   "small_tiles"     0 | 1   use 128/64/32-row tiles for the ragged tail of an expert
+ *   "probe_k_resident" 0 | 1  timing probe only: the GEMMs re-read their first K tile at every K step
+ *                             (operands stay cache resident, RESULTS ARE MEANINGLESS); default 0
  *   "y_fp32"          0 | 1   dtype of y_perm / y_shared: 1 (default) fp32, 0 bf16.  bf16 halves the
  *                             traffic of the down projection's store and of the combine's loads, but
  *                             rounds each expert output to 8 mantissa bits before the weighted sum

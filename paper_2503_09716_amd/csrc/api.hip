@@ -26,7 +26,7 @@ struct ProfRec {
 struct moe_ctx {
     int device = 0;
     char err[512] = {0};
-    GemmConfig gemm{2, 8, 1, 1};
+    GemmConfig gemm{2, 4, 8, 1, 1, 0};
     bool y_fp32 = true;    // dtype of y_perm / y_shared
     bool out_fp32 = false; // dtype of the layer output
     // Ring of device pointer tables [3][MAX_GROUPS] (W1p, W3p, W2p), each with a pinned host
@@ -204,6 +204,7 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     a.xcd_remap = c->gemm.xcd_remap;
     a.small_tiles = c->gemm.small_tiles;
     a.out_fp32 = 0;
+    a.k_step_bytes = c->gemm.probe_k_resident ? 0 : 64;
     // GEMM 1: [rows, H] x W1p/W3p [F, H] -> h [rows, F]
     a.a_routed = (const char*)(row_token ? x : x_perm);
     a.a_shared = (const char*)x;
@@ -287,10 +288,12 @@ size_t moe_workspace_bytes(const moe_shape* s) {
 moe_status moe_set_option(moe_ctx* c, const char* key, int32_t v) {
     if (!c || !key) return MOE_E_ARG;
     c->err[0] = 0;
-    if (!strcmp(key, "gemm_wave_rows") && (v == 1 || v == 2)) { c->gemm.wave_rows = v; return MOE_OK; }
+    if (!strcmp(key, "gemm_wave_rows") && (v == 1 || v == 2 || v == 4)) { c->gemm.wave_rows = v; return MOE_OK; }
+    if (!strcmp(key, "gemm_waves") && (v == 4 || v == 8)) { c->gemm.waves = v; return MOE_OK; }
     if (!strcmp(key, "gemm_group_m") && v >= 1 && v <= 64) { c->gemm.group_m = v; return MOE_OK; }
     if (!strcmp(key, "xcd_remap") && (v == 0 || v == 1)) { c->gemm.xcd_remap = v; return MOE_OK; }
     if (!strcmp(key, "small_tiles") && (v == 0 || v == 1)) { c->gemm.small_tiles = v; return MOE_OK; }
+    if (!strcmp(key, "probe_k_resident") && (v == 0 || v == 1)) { c->gemm.probe_k_resident = v; return MOE_OK; }
     if (!strcmp(key, "y_fp32") && (v == 0 || v == 1)) { c->y_fp32 = v != 0; return MOE_OK; }
     if (!strcmp(key, "out_fp32") && (v == 0 || v == 1)) { c->out_fp32 = v != 0; return MOE_OK; }
     return fail(c, MOE_E_ARG, "unknown option or value out of range: %s=%d", key, (int)v);

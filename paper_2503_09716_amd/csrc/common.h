@@ -49,13 +49,16 @@ struct GemmArgs {
     int32_t xcd_remap;
     int32_t small_tiles;       // 1: a short tail tile runs the 128/64/32-row variant
     int32_t out_fp32;          // GEMM2: 1 = y stored as fp32, 0 = bf16 (GEMM1 always stores bf16)
+    int32_t k_step_bytes;      // bytes the K pointers advance per tile: BK*2; 0 only for the cache-resident timing probe
 };
 
 struct GemmConfig {
-    int wave_rows;    // 1 or 2
+    int wave_rows;    // rows of the wave grid: 1 or 2 with 4 waves, 2 or 4 with 8 waves
+    int waves;        // wavefronts per workgroup: 4 or 8
     int group_m;
     int xcd_remap;
     int small_tiles;
+    int probe_k_resident;  // timing probe: every K step re-reads the first tile (results are meaningless)
 };
 
 // Upper bound on the number of m-tiles for any routing outcome.

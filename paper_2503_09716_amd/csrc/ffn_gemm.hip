@@ -3,22 +3,28 @@
 // accumulated batch, so each expert's rows form a tall matrix and the GEMMs are compute bound.)
 //
 //   GEMM 1 (gated):  h[r, f]  = silu(X_e[r,:] . W1p_e[f,:]) * (X_e[r,:] . W3p_e[f,:])      -> bf16
-//   GEMM 2        :  y[r, n]  = h[r,:] . W2p_e[n,:]                                        -> bf16
+//   GEMM 2        :  y[r, n]  = h[r,:] . W2p_e[n,:]                                        -> fp32 / bf16
 // Both operands are K-contiguous ("packed" weights), so one tile routine serves both.
 //
-// Tile routine (one workgroup = 4 wavefronts, one per SIMD, up to 512 registers each):
+// Tile routine (one workgroup = NW wavefronts in a WM x WN grid):
 //   * macro tile: BM rows of X (256/128/64/32) x 256 rows of W (GEMM 1: 128 gate + 128 up rows,
-//     so the SiLU-gate product is formed in registers), K step 64.
-//   * global -> LDS with global_load_lds_dwordx4 (no VGPR round trip), two LDS stages
-//     (2 x 64 KiB at BM = 256), one barrier per K step.
-//   * LDS layout: 128-byte rows (64 bf16), the eight 16-byte pieces of a row XOR-swizzled by
-//     (row ^ row/8) & 7 so that the 16-byte MFMA operand reads of 16 consecutive rows fall in
-//     distinct banks.  The swizzle is applied by choosing which global piece each lane of the
+//     so the SiLU-gate product is formed in registers); K advances in sub-tiles of 32.
+//   * global -> LDS with global_load_lds_dwordx4 (no VGPR round trip) into a ring of NS = 4
+//     LDS stages (4 x 32 KiB at BM = 256): the loads of sub-tile t+3 are issued while sub-tile t
+//     is multiplied, so HBM latency has three sub-tiles of MFMA work to hide behind, and they
+//     are spread between the MFMAs (one every few) instead of bursting after the barrier.
+//     One barrier per sub-tile; s_waitcnt vmcnt(n) waits only for the sub-tile needed next.
+//   * LDS layout: 64-byte rows (32 bf16), the four 16-byte pieces of a row XOR-swizzled by
+//     (row / 4) & 3 so the 16-byte MFMA operand reads of 16 consecutive rows fall in distinct
+//     banks.  The swizzle is applied by choosing which global piece each lane of the
 //     direct-to-LDS load fetches, since the LDS side of that load is fixed (lane * 16 bytes).
 //   * v_mfma_f32_32x32x16_bf16 with W as the row (A) operand and X as the column (B) operand:
 //     a lane's 16 accumulator registers then belong to ONE output row.  W rows are placed in
 //     LDS in the order that makes those 16 registers 16 CONSECUTIVE output columns, so the
-//     epilogue writes 2 x 16-byte stores per 32x32 block straight from registers.
+//     epilogue writes 16-byte stores straight from registers.
+//   * operand fragments are double-buffered in registers; the instruction stream is laid out
+//     by hand in small groups {MFMAs, one LDS read, one global load} fenced by scheduling
+//     barriers, so the matrix pipe always has independent work queued.
 //   * ragged tails: rows past the end of a group are clamped on load and masked on store;
 //     short tails use the 128/64/32-row variants so padded MFMA work stays small.
 //
@@ -33,50 +39,68 @@
 namespace moe {
 namespace {
 
-constexpr int BK = 64;              // K elements per LDS stage
+constexpr int BK = 32;              // K elements per LDS stage
+constexpr int ROWB = BK * 2;        // bytes per LDS row
 constexpr int WROWS = 256;          // W rows per macro tile
-constexpr int MAX_LDS = 2 * (256 + WROWS) * BK * 2;  // 131072 bytes
+constexpr int NS = 4;               // LDS ring depth
+constexpr int MAX_STAGE = (256 + WROWS) * ROWB;          // 32 KiB
+constexpr int MAX_LDS = NS * MAX_STAGE;
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
+typedef __attribute__((address_space(3))) char* lds_t;
 
-__device__ __forceinline__ void load16_to_lds(const char* g, char* lds_wave_base) {
-    // 64 lanes x 16 bytes land at lds_wave_base + lane*16 (the LDS address is wave-uniform).
-    __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)lds_wave_base, 16, 0, 0);
+// Buffer descriptor over [ptr, ptr + 4 GiB - 1) for raw (untyped) accesses.  The pointer is
+// wave-uniform by construction; readfirstlane tells the compiler so (otherwise every load is
+// wrapped in a waterfall loop).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t uniform_rsrc(const void* ptr) {
+    const uint64_t v = (uint64_t)ptr;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return __builtin_amdgcn_make_buffer_rsrc((void*)(((uint64_t)hi << 32) | lo), 0, 0xFFFFFFFF, 0x00020000);
 }
 
-__device__ __forceinline__ void wait_loads_and_sync() {
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's direct-to-LDS loads have landed
-    __syncthreads();
+// 64 lanes x 16 bytes from (descriptor base + voff + soff) to LDS at l + lane*16 (l wave-uniform).
+// The 16-byte form exists on gfx950 only; the host pass of hipcc must not see it.
+__device__ __forceinline__ void buffer_load16_to_lds(__amdgpu_buffer_rsrc_t rsrc, lptr_t l, uint32_t voff, int soff) {
+#if defined(__gfx950__)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, l, 16, voff, soff, 0, 0);
+#endif
 }
 
-// Scheduling pattern for one K sub-step: after each MFMA place (at most) one LDS read and, while
-// direct-to-LDS loads remain, `VPER` of them.  Emitted through templates because the builtin
-// only takes literal constants.
-template <int N, int NMFMA, int NREAD, int NLOAD>
-__device__ __forceinline__ void sched_substep() {
-    if constexpr (N < NMFMA) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                       // 1 MFMA
-        if constexpr (N < NREAD) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 LDS read
-        constexpr int VPER = (NLOAD + NMFMA - 1) / NMFMA;
-        if constexpr (N * VPER < NLOAD)
-            __builtin_amdgcn_sched_group_barrier(0x070, (N + 1) * VPER <= NLOAD ? VPER : NLOAD - N * VPER, 0);  // VMEM
-        sched_substep<N + 1, NMFMA, NREAD, NLOAD>();
-    }
+// Hand-over point of the LDS ring: wait until at most N of this wave's direct-to-LDS loads
+// are still in flight (they retire in order, so everything older has landed) and until this
+// wave's own LDS reads have returned, then meet the other waves.  A bare s_barrier is used
+// instead of __syncthreads(), whose release fence would drain ALL outstanding loads and so
+// serialise the ring; the empty asm statements keep the compiler from moving LDS accesses
+// across the barrier.
+template <int N>
+__device__ __forceinline__ void ring_sync() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0070);  // vmcnt(N) lgkmcnt(0), gfx9 encoding
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
 }
 
-// WM x (4/WM) wave grid; TI = 32-row X blocks per wave; GATED = GEMM 1.
-template <int WM, int TI, bool GATED>
+// NW wavefronts as a WM x (NW/WM) grid; TI = 32-row X blocks per wave; GATED = GEMM 1.
+template <int NW, int WM, int TI, bool GATED>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, const int n_tile, char* lds) {
-    constexpr int WN = 4 / WM;
+    constexpr int WN = NW / WM;
     constexpr int TJ = 8 / WN;               // 32-row W blocks per wave
     constexpr int BM = WM * TI * 32;
-    constexpr int XBYTES = BM * BK * 2;
-    constexpr int STAGE = XBYTES + WROWS * BK * 2;
-    constexpr int NLX = BM / 32;             // direct-to-LDS loads per wave per stage, X part
-    constexpr int NLW = WROWS / 32;          // ... W part
+    constexpr int NLX = (BM / 16 + NW - 1) / NW;   // X wave-loads (16 rows x 64 B) per wave per stage
+    constexpr int NQX = NLX * NW;                  // X wave-loads per stage (region padded to a multiple of NW)
+    constexpr int XBYTES = NQX * 1024;
+    constexpr int NL = NLX + (WROWS / 16) / NW;    // all wave-loads per wave per stage
+    constexpr int NL0 = NL / 2;                    // issued in the first half of an iteration
+    constexpr int RING_STRIDE = NL * NW * 1024;    // bytes per ring stage
+    static_assert(NS * RING_STRIDE <= MAX_LDS, "ring does not fit");
     constexpr int BN = GATED ? 128 : 256;    // output columns per macro tile
     constexpr int TJH = TJ / 2;              // GATED: gate blocks per wave (= up blocks per wave)
+    constexpr int NMFMA = TI * TJ;           // MFMAs per half iteration (one K step of 16)
+    constexpr int NREAD = TI + TJ;           // LDS fragment reads per half iteration
+    static_assert(TJ >= 1 && (!GATED || TJ >= 2), "wave grid too wide");
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -85,66 +109,64 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
     const int n0 = n_tile * BN;
     const bool shared = d.srow >= 0;
     const int nseg = (!GATED && shared) ? p.nseg_shared : 1;
-
-    // ------------------------------------------------------------------ loader setup
-    const int lrow = lane >> 3, lslot = lane & 7;
-    uint32_t xoff[NLX], woff[NLW];
-#pragma unroll
-    for (int i = 0; i < NLX; ++i) {
-        const int q = i * 4 + wave;               // wave-load index inside the X region
-        int r = q * 8 + lrow;                     // tile row 0..BM-1
-        if (r > d.nrows - 1) r = d.nrows - 1;     // clamp: padded rows re-read the last valid row
-        int grow = d.row0 + r;
-        if (GATED && !shared && p.row_token) grow = p.row_token[grow];
-        const int c = lslot ^ ((lrow ^ q) & 7);   // logical 16-byte piece that lands in slot lslot
-        xoff[i] = (uint32_t)grow * (uint32_t)(K * 2) + (uint32_t)(c * 16);
-    }
-#pragma unroll
-    for (int i = 0; i < NLW; ++i) {
-        const int q = i * 4 + wave;               // wave-load index inside the W region; block = i
-        const int rho = wave * 8 + lrow;          // LDS row inside the 32-row block = MFMA row
-        const int nloc = ((rho >> 2) & 1) * 16 + (rho >> 3) * 4 + (rho & 3);
-        int n = n0 + (GATED ? (i & 3) : i) * 32 + nloc;
-        if (n > N - 1) n = N - 1;
-        const int c = lslot ^ ((lrow ^ q) & 7);
-        woff[i] = (uint32_t)n * (uint32_t)(K * 2) + (uint32_t)(c * 16);
-    }
+    const int kstep = p.k_step_bytes;
     const char* const a_base = shared ? p.a_shared : p.a_routed;
     const size_t a_seg_stride = (size_t)p.T * (size_t)K * 2;
-    const char* a_ptr = a_base;
-    const char* wa_ptr = nullptr;
-    const char* wb_ptr = nullptr;
 
-    // Enqueues the direct-to-LDS loads of one K tile and moves the (wave-uniform) source
-    // pointers to the next tile.  Branch-free, so the loads can be scheduled between MFMAs.
-    auto issue = [&](const int stage) {
-        char* xs = lds + stage * STAGE;
-        char* ws = xs + XBYTES;
+    // ------------------------------------------------------------------ loader setup
+    // Wave-load q fills LDS bytes [q*1024, q*1024+1024) of a stage: 16 rows x 4 pieces.
+    // Lane l supplies row q*16 + l/4, slot l%4, which must hold logical piece (l%4) ^ ((l/16)&3).
+    // This wave owns q = i*NW + wave; the X region is padded to a multiple of NW wave-loads so
+    // that load i is an X load for i < NLX and a W load otherwise, for every wave.
+    // Loads are buffer loads: address = operand base (SGPR descriptor) + per-lane offset (VGPR,
+    // fixed for the whole tile) + K offset (SGPR, advanced per sub-tile), so the K loop needs no
+    // vector address arithmetic at all.
+    const int lrow = lane >> 2;
+    const int lpiece = (lane & 3) ^ ((lane >> 4) & 3);
+    uint32_t loff[NL];
 #pragma unroll
-        for (int i = 0; i < NLX; ++i) load16_to_lds(a_ptr + xoff[i], xs + (i * 4 + wave) * 1024);
-#pragma unroll
-        for (int i = 0; i < NLW; ++i)
-            load16_to_lds(((GATED && i >= 4) ? wb_ptr : wa_ptr) + woff[i], ws + (i * 4 + wave) * 1024);
-        a_ptr += BK * 2;
-        wa_ptr += BK * 2;
-        if (GATED) wb_ptr += BK * 2;
+    for (int i = 0; i < NL; ++i) {
+        const int q = i * NW + wave;
+        if (i < NLX) {
+            int r = q * 16 + lrow;
+            if (r > d.nrows - 1) r = d.nrows - 1;     // padded rows re-read the last valid row
+            int grow = d.row0 + r;
+            if (GATED && !shared && p.row_token) grow = p.row_token[grow];
+            loff[i] = (uint32_t)grow * (uint32_t)(K * 2) + (uint32_t)(lpiece * 16);
+        } else {
+            const int wr = (q - NQX) * 16 + lrow;     // LDS row inside the W region, 0..255
+            const int blk = wr >> 5, rho = wr & 31;   // 32-row block, MFMA row inside it
+            const int nloc = ((rho >> 2) & 1) * 16 + (rho >> 3) * 4 + (rho & 3);
+            int n = n0 + (GATED ? (blk & 3) : blk) * 32 + nloc;
+            if (n > N - 1) n = N - 1;
+            loff[i] = (uint32_t)n * (uint32_t)(K * 2) + (uint32_t)(lpiece * 16);
+        }
+    }
+    lds_t const ring = (lds_t)lds;
+    __amdgpu_buffer_rsrc_t rs_x, rs_w, rs_u;   // X, W (gate / down), W (up)
+    int koff = 0;                              // byte offset along K of the sub-tile being loaded
+
+    // Enqueues direct-to-LDS load i of the sub-tile at `koff` into ring stage `stage`.
+    auto issue_one = [&](const int i, const int stage) __attribute__((always_inline)) {
+        lptr_t dst = (lptr_t)(ring + stage * RING_STRIDE + (i * NW + wave) * 1024);
+        if (i < NLX) buffer_load16_to_lds(rs_x, dst, loff[i], koff);
+        else if (GATED && (i - NLX) * NW >= 8) buffer_load16_to_lds(rs_u, dst, loff[i], koff);
+        else buffer_load16_to_lds(rs_w, dst, loff[i], koff);
     };
 
     // ------------------------------------------------------------------ reader setup
+    // Lane l reads row (l & 31) of a 32-row block, logical piece kk*2 + (l >> 5), stored at
+    // slot piece ^ ((row / 4) & 3).  Block bases are multiples of 32 rows, so the swizzle term
+    // depends on the lane only.
     const int rl = lane & 31, g = lane >> 5;
-    const int tsw = (g ^ (rl & 7) ^ (rl >> 3)) & 7;
-    // offU[u] : byte offset inside a 32-row block for swizzle selector u (piece = tsw ^ 2u)
-    uint32_t offU[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) offU[u] = (uint32_t)(rl * 128 + ((tsw ^ (2 * u)) << 4));
-    // first X / W block of this wave and its parity (parity flips the piece index by 4)
     const int bx0 = wm * TI;
     const int bw0 = GATED ? wn * TJH : wn * TJ;
-    uint32_t offX[4], offW[4];
+    uint32_t offX[2], offW[2];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-        offX[kk] = ((bx0 & 1) ? offU[kk ^ 2] : offU[kk]) + (uint32_t)(bx0 * 4096);
-        offW[kk] = ((bw0 & 1) ? offU[kk ^ 2] : offU[kk]) + (uint32_t)(XBYTES + bw0 * 4096);
+    for (int kk = 0; kk < 2; ++kk) {
+        const uint32_t o = (uint32_t)(rl * ROWB + ((((kk << 1) | g) ^ ((rl >> 2) & 3)) << 4));
+        offX[kk] = o + (uint32_t)(bx0 * 32 * ROWB);
+        offW[kk] = o + (uint32_t)(XBYTES + bw0 * 32 * ROWB);
     }
 
     f32x16 acc[TJ][TI];
@@ -155,77 +177,103 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
 
-    // Software pipeline (one K tile = 4 sub-steps kk of 16):
-    //   top of iteration : direct-to-LDS loads of the NEXT tile go out, interleaved with the
-    //                      MFMAs of kk = 0 so the matrix pipe never waits for their issue
-    //   kk = 0..2        : LDS reads of kk+1 are interleaved with the MFMAs of kk
-    //   before kk = 3    : vmcnt(0) + barrier (next tile landed, everyone is done reading this
-    //                      one), then the kk = 0 fragments of the NEXT tile are read while the
-    //                      MFMAs of kk = 3 run.
-    // Fragments live in two register buffers that alternate per sub-step.
-    auto load_frags = [&](const char* base, const int kk, bf16x8 (&xf)[TI], bf16x8 (&wf)[TJ]) {
-#pragma unroll
-        for (int i = 0; i < TI; ++i)
-            xf[i] = *reinterpret_cast<const bf16x8*>(base + offX[kk ^ ((i & 1) << 1)] + i * 4096);
-#pragma unroll
-        for (int j = 0; j < TJ; ++j) {
+    bf16x8 xf[2][TI], wf[2][TJ];   // fragment double buffer
+
+    // Fragment read number r of K step kk from the stage at `base` into buffer `buf`.
+    typedef __attribute__((address_space(3))) const bf16x8* frag_ptr_t;
+    auto read_frag = [&](const int stage, const int kk, const int buf, const int r) __attribute__((always_inline)) {
+        lds_t base = ring + stage * RING_STRIDE;
+        if (r < TI) {
+            xf[buf][r] = *(frag_ptr_t)(base + offX[kk] + r * 32 * ROWB);
+        } else {
+            const int j = r - TI;
             // relative W block: GEMM 2: j; GEMM 1: gate blocks j < TJH, up blocks 4 + (j - TJH)
             const int rel = GATED ? (j < TJH ? j : 4 + (j - TJH)) : j;
-            wf[j] = *reinterpret_cast<const bf16x8*>(base + offW[kk ^ ((rel & 1) << 1)] + rel * 4096);
+            wf[buf][j] = *(frag_ptr_t)(base + offW[kk] + rel * 32 * ROWB);
         }
     };
-    auto mfmas = [&](const bf16x8 (&xf)[TI], const bf16x8 (&wf)[TJ]) {
-#pragma unroll
-        for (int j = 0; j < TJ; ++j)
-#pragma unroll
-            for (int i = 0; i < TI; ++i)
-                acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], xf[i], acc[j][i], 0, 0, 0);
-    };
-    constexpr int NMFMA = TI * TJ;      // per sub-step
-    constexpr int NREAD = TI + TJ;      // LDS reads per sub-step
-    constexpr int NLOAD = NLX + NLW;    // direct-to-LDS loads per tile per wave
 
-    const int KT = K / BK;
-    bf16x8 xf0[TI], wf0[TJ], xf1[TI], wf1[TJ];
-    // MORE = another K tile follows (the last iteration is peeled so the body has no branches).
-    auto body = [&](auto more_tag, const int kt) {
-        constexpr bool MORE = decltype(more_tag)::value;
-        const char* cur = lds + (kt & 1) * STAGE;
-        const char* nxt = lds + ((kt & 1) ^ 1) * STAGE;
-        // ---- kk = 0 (+ global loads of the next tile, + LDS reads of kk = 1)
-        if (MORE) issue((kt & 1) ^ 1);
-        load_frags(cur, 1, xf1, wf1);
-        mfmas(xf0, wf0);
-        sched_substep<0, NMFMA, NREAD, MORE ? NLOAD : 0>();
-        __builtin_amdgcn_sched_barrier(0);
-        // ---- kk = 1
-        load_frags(cur, 2, xf0, wf0);
-        mfmas(xf1, wf1);
-        sched_substep<0, NMFMA, NREAD, 0>();
-        __builtin_amdgcn_sched_barrier(0);
-        // ---- kk = 2
-        load_frags(cur, 3, xf1, wf1);
-        mfmas(xf0, wf0);
-        sched_substep<0, NMFMA, NREAD, 0>();
-        __builtin_amdgcn_sched_barrier(0);
-        // ---- kk = 3: hand-over to the next tile
-        wait_loads_and_sync();
-        if (MORE) load_frags(nxt, 0, xf0, wf0);
-        mfmas(xf1, wf1);
-        sched_substep<0, NMFMA, MORE ? NREAD : 0, 0>();
-        __builtin_amdgcn_sched_barrier(0);
+    // One half iteration: the NMFMA MFMAs of one K step from buffer `buf`, interleaved with the
+    // NREAD fragment reads of the next K step (RD) and with direct-to-LDS loads LD0..LD1-1 (LD).
+    // Laid out as NMFMA / G groups of {G MFMAs, <= 1..2 reads, <= 1 load}.
+    auto half = [&](auto rd_tag, auto ld_tag, auto ld0_tag, auto ld1_tag, const int buf, const int rd_stage,
+                    const int rd_kk, const int ld_stage) __attribute__((always_inline)) {
+        constexpr bool RD = decltype(rd_tag)::value;
+        constexpr bool LD = decltype(ld_tag)::value;
+        constexpr int LD0 = decltype(ld0_tag)::value, LD1 = decltype(ld1_tag)::value;
+        constexpr int NGRP = NMFMA >= 8 ? 8 : NMFMA;          // groups per half
+        constexpr int G = NMFMA / NGRP;                        // MFMAs per group
+        constexpr int RPG0 = (NREAD + NGRP - 1) / NGRP;
+        constexpr int RPG = RPG0 < 2 ? 2 : RPG0;               // reads per group (front-loaded)
+        constexpr int NLD = LD1 - LD0;
+#pragma unroll
+        for (int s = 0; s < NGRP; ++s) {
+#pragma unroll
+            for (int m = s * G; m < (s + 1) * G; ++m) {
+                const int j = m / TI, i = m % TI;
+                acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][j], xf[buf][i], acc[j][i], 0, 0, 0);
+            }
+            if (RD) {
+#pragma unroll
+                for (int r = s * RPG; r < (s + 1) * RPG && r < NREAD; ++r) read_frag(rd_stage, rd_kk, buf ^ 1, r);
+            }
+            if (LD) {
+                // spread NLD loads over the NGRP groups
+#pragma unroll
+                for (int l = (s * NLD) / NGRP; l < ((s + 1) * NLD) / NGRP; ++l) issue_one(LD0 + l, ld_stage);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
+    using T_ = std::true_type;
+    using F_ = std::false_type;
+
+    const int KT = K / BK;   // sub-tiles per segment (>= 2)
+    using I0 = std::integral_constant<int, 0>;
     // GEMM 2 on shared experts walks `nseg` K-concatenated segments (one per shared expert);
     // every other tile has one segment.  The pipeline drains and restarts between segments.
     for (int seg = 0; seg < nseg; ++seg) {
-        a_ptr = a_base + (size_t)seg * a_seg_stride;
-        wa_ptr = (const char*)p.w_a[d.group + seg];
-        if (GATED) wb_ptr = (const char*)p.w_b[d.group];
-        issue(0);
-        wait_loads_and_sync();
-        load_frags(lds, 0, xf0, wf0);
-        for (int kt = 0; kt < KT - 1; ++kt) body(std::true_type{}, kt);
-        body(std::false_type{}, KT - 1);
+        // the descriptors span 4 GiB - 1; bounds are kept by the row clamps above
+        rs_x = uniform_rsrc(a_base + (size_t)seg * a_seg_stride);
+        rs_w = uniform_rsrc(p.w_a[d.group + seg]);
+        if (GATED) rs_u = uniform_rsrc(p.w_b[d.group]);
+        koff = 0;
+        // prologue: sub-tiles 0 .. NS-2 go out, wait for sub-tile 0
+#pragma unroll
+        for (int s = 0; s < NS - 1; ++s) {
+            if (s < KT) {
+#pragma unroll
+                for (int i = 0; i < NL; ++i) issue_one(i, s);
+                koff += kstep;
+            }
+        }
+        if (KT >= NS - 1) ring_sync<(NS - 2) * NL>();
+        else ring_sync<0>();
+#pragma unroll
+        for (int r = 0; r < NREAD; ++r) read_frag(0, 0, 0, r);
+
+        int t = 0;
+        // steady state: sub-tile t is multiplied, sub-tile t+NS-1 is loaded
+        for (; t + NS - 1 < KT; ++t) {
+            const int cur = t % NS, nxt = (t + 1) % NS, ld = (t + NS - 1) % NS;
+            half(T_{}, T_{}, I0{}, std::integral_constant<int, NL0>{}, 0, cur, 1, ld);
+            // Sub-tile t+1 has landed once only the younger loads are outstanding.  The same
+            // barrier frees stage `cur` for the loads of the NEXT iteration: its last reads were
+            // issued above and have returned (lgkmcnt(0)) before any wave passes.
+            ring_sync<(NS - 3) * NL + NL0>();
+            half(T_{}, T_{}, std::integral_constant<int, NL0>{}, std::integral_constant<int, NL>{}, 1, nxt, 0, ld);
+            koff += kstep;
+        }
+        // tail: nothing left to load; conservative waits
+        for (; t < KT - 1; ++t) {
+            const int cur = t % NS, nxt = (t + 1) % NS;
+            half(T_{}, F_{}, I0{}, I0{}, 0, cur, 1, 0);
+            ring_sync<0>();
+            half(T_{}, F_{}, I0{}, I0{}, 1, nxt, 0, 0);
+        }
+        half(T_{}, F_{}, I0{}, I0{}, 0, t % NS, 1, 0);
+        ring_sync<0>();    // every wave is done reading the ring before the next segment refills it
+        half(F_{}, F_{}, I0{}, I0{}, 1, 0, 0, 0);
     }
 
     // ------------------------------------------------------------------ epilogue
@@ -253,6 +301,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
                 }
                 *reinterpret_cast<bf16x8*>(orow + (size_t)col * 2) = o0;
                 *reinterpret_cast<bf16x8*>(orow + (size_t)col * 2 + 16) = o1;
+                __builtin_amdgcn_sched_barrier(0);   // one block at a time: keeps accumulator reads from piling up
             }
         } else if (p.out_fp32) {
             orow = out + (size_t)(orow_base + r) * (size_t)N * 4;
@@ -267,6 +316,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
                     for (int e = 0; e < 4; ++e) o[e] = acc[j][i][q * 4 + e];
                     *reinterpret_cast<f32x4*>(orow + (size_t)col * 4 + q * 16) = o;
                 }
+                __builtin_amdgcn_sched_barrier(0);
             }
         } else {
 #pragma unroll
@@ -281,6 +331,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
                 }
                 *reinterpret_cast<bf16x8*>(orow + (size_t)col * 2) = o0;
                 *reinterpret_cast<bf16x8*>(orow + (size_t)col * 2 + 16) = o1;
+                __builtin_amdgcn_sched_barrier(0);   // one block at a time: keeps accumulator reads from piling up
             }
         }
     }
@@ -296,9 +347,8 @@ __device__ __forceinline__ int tile_order(const int wg, const int total, const i
     return (q << 8) + ((r & 7) << 5) + (r >> 3);
 }
 
-template <int WM, bool GATED>
-__global__ __launch_bounds__(256, 1) void ffn_gemm_kernel(const GemmArgs p) {
-    extern __shared__ __attribute__((aligned(1024))) char lds[];
+// Tile picked by this workgroup (false: nothing to do).
+__device__ __forceinline__ bool pick_tile(const GemmArgs& p, const bool gated, TileDesc& d, int& n_tile) {
     const int L = tile_order(blockIdx.x, gridDim.x, p.xcd_remap);
     // consecutive positions: group_m m-tiles first, then along n
     const int per_super = p.group_m * p.n_tiles;
@@ -306,21 +356,50 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_kernel(const GemmArgs p) {
     const int rem = L - sr * per_super;
     const int mt0 = sr * p.group_m;
     const int gm = min(p.group_m, p.max_mtiles - mt0);
-    const int n_tile = rem / gm;
+    n_tile = rem / gm;
     const int mt = mt0 + (rem - n_tile * gm);
-    const int count = GATED ? p.plan->n_gate_up : p.plan->n_down;
-    if (mt >= count) return;  // uniform for the workgroup
-    const TileDesc d = p.descs[mt];
+    const int count = gated ? p.plan->n_gate_up : p.plan->n_down;
+    if (mt >= count) return false;  // uniform for the workgroup
+    d = p.descs[mt];
+    return true;
+}
+
+// 4 wavefronts (one per SIMD, up to 512 registers each), wave grid WM x 4/WM.
+template <int WM, bool GATED>
+__global__ __launch_bounds__(256, 1) void ffn_gemm_kernel(const GemmArgs p) {
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    TileDesc d;
+    int n_tile;
+    if (!pick_tile(p, GATED, d, n_tile)) return;
     const int blocks = p.small_tiles ? (d.nrows + 31) >> 5 : 8;  // 32-row blocks that hold real rows
     if (WM == 2) {
-        if (blocks > 4) gemm_tile<2, 4, GATED>(p, d, n_tile, lds);
-        else if (blocks > 2) gemm_tile<2, 2, GATED>(p, d, n_tile, lds);
-        else gemm_tile<2, 1, GATED>(p, d, n_tile, lds);
+        if (blocks > 4) gemm_tile<4, 2, 4, GATED>(p, d, n_tile, lds);
+        else if (blocks > 2) gemm_tile<4, 2, 2, GATED>(p, d, n_tile, lds);
+        else gemm_tile<4, 2, 1, GATED>(p, d, n_tile, lds);
     } else {
-        if (blocks > 4) gemm_tile<1, 8, GATED>(p, d, n_tile, lds);
-        else if (blocks > 2) gemm_tile<1, 4, GATED>(p, d, n_tile, lds);
-        else if (blocks > 1) gemm_tile<1, 2, GATED>(p, d, n_tile, lds);
-        else gemm_tile<1, 1, GATED>(p, d, n_tile, lds);
+        if (blocks > 4) gemm_tile<4, 1, 8, GATED>(p, d, n_tile, lds);
+        else if (blocks > 2) gemm_tile<4, 1, 4, GATED>(p, d, n_tile, lds);
+        else if (blocks > 1) gemm_tile<4, 1, 2, GATED>(p, d, n_tile, lds);
+        else gemm_tile<4, 1, 1, GATED>(p, d, n_tile, lds);
+    }
+}
+
+// 8 wavefronts (two per SIMD, up to 256 registers each), wave grid WM x 8/WM: while one wave
+// of a SIMD waits at the ring barrier or on LDS, the other keeps the matrix pipe fed.
+template <int WM, bool GATED>
+__global__ __launch_bounds__(512, 2) void ffn_gemm_kernel8(const GemmArgs p) {
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    TileDesc d;
+    int n_tile;
+    if (!pick_tile(p, GATED, d, n_tile)) return;
+    const int blocks = p.small_tiles ? (d.nrows + 31) >> 5 : 8;
+    if (WM == 2) {
+        if (blocks > 4) gemm_tile<8, 2, 4, GATED>(p, d, n_tile, lds);
+        else if (blocks > 2) gemm_tile<8, 2, 2, GATED>(p, d, n_tile, lds);
+        else gemm_tile<8, 2, 1, GATED>(p, d, n_tile, lds);
+    } else {
+        if (blocks > 4) gemm_tile<8, 4, 2, GATED>(p, d, n_tile, lds);
+        else gemm_tile<8, 4, 1, GATED>(p, d, n_tile, lds);
     }
 }
 
@@ -388,6 +467,10 @@ hipError_t ffn_gemm_init() {
     SET_LDS((ffn_gemm_kernel<2, false>))
     SET_LDS((ffn_gemm_kernel<1, true>))
     SET_LDS((ffn_gemm_kernel<1, false>))
+    SET_LDS((ffn_gemm_kernel8<2, true>))
+    SET_LDS((ffn_gemm_kernel8<2, false>))
+    SET_LDS((ffn_gemm_kernel8<4, true>))
+    SET_LDS((ffn_gemm_kernel8<4, false>))
 #undef SET_LDS
     return hipSuccess;
 }
@@ -401,14 +484,24 @@ hipError_t launch_ffn_plan(const moe_shape& s, const int32_t* offsets, PlanHeade
 }
 
 hipError_t launch_ffn_gemm(bool gated, const GemmArgs& a, const GemmConfig& cfg, hipStream_t st) {
-    const dim3 grid((unsigned)(a.max_mtiles * a.n_tiles)), block(256);
-    if (cfg.wave_rows == 2) {
-        if (gated) hipLaunchKernelGGL((ffn_gemm_kernel<2, true>), grid, block, MAX_LDS, st, a);
-        else hipLaunchKernelGGL((ffn_gemm_kernel<2, false>), grid, block, MAX_LDS, st, a);
+    const dim3 grid((unsigned)(a.max_mtiles * a.n_tiles));
+#define LAUNCH(KERNEL, THREADS) hipLaunchKernelGGL((KERNEL), grid, dim3(THREADS), MAX_LDS, st, a)
+    if (cfg.waves == 8) {
+        if (cfg.wave_rows == 4) {
+            if (gated) LAUNCH((ffn_gemm_kernel8<4, true>), 512);
+            else LAUNCH((ffn_gemm_kernel8<4, false>), 512);
+        } else {
+            if (gated) LAUNCH((ffn_gemm_kernel8<2, true>), 512);
+            else LAUNCH((ffn_gemm_kernel8<2, false>), 512);
+        }
+    } else if (cfg.wave_rows == 2) {
+        if (gated) LAUNCH((ffn_gemm_kernel<2, true>), 256);
+        else LAUNCH((ffn_gemm_kernel<2, false>), 256);
     } else {
-        if (gated) hipLaunchKernelGGL((ffn_gemm_kernel<1, true>), grid, block, MAX_LDS, st, a);
-        else hipLaunchKernelGGL((ffn_gemm_kernel<1, false>), grid, block, MAX_LDS, st, a);
+        if (gated) LAUNCH((ffn_gemm_kernel<1, true>), 256);
+        else LAUNCH((ffn_gemm_kernel<1, false>), 256);
     }
+#undef LAUNCH
     return hipGetLastError();
 }
 

@@ -127,7 +127,7 @@ def test_permute(moe, T, E, k, skew):
     np.testing.assert_array_equal(np.bincount(perm.cpu().numpy() // k, minlength=T), np.full(T, k))
 
 
-def run_ffn_stage(moe, cfg, idx_h, wave_rows=2, small_tiles=1, use_row_token=False, y_fp32=True):
+def run_ffn_stage(moe, cfg, idx_h, wave_rows=2, small_tiles=1, use_row_token=False, y_fp32=True, waves=4):
     """Runs moe_permute + moe_grouped_ffn for a given routing; returns (y_perm, y_shared, perm, li)."""
     from paper_2503_09716_amd import shape_of
     shape = shape_of(cfg)
@@ -146,6 +146,7 @@ def run_ffn_stage(moe, cfg, idx_h, wave_rows=2, small_tiles=1, use_row_token=Fal
     ydt = torch.float32 if y_fp32 else torch.bfloat16
     y = torch.full((R, cfg.H), float("nan"), dtype=ydt, device="cuda")
     ysh = torch.full((cfg.T, cfg.H), float("nan"), dtype=ydt, device="cuda") if cfg.num_shared else None
+    moe.set_option("gemm_waves", waves)
     moe.set_option("gemm_wave_rows", wave_rows)
     moe.set_option("small_tiles", small_tiles)
     moe.set_option("y_fp32", 1 if y_fp32 else 0)
@@ -154,31 +155,41 @@ def run_ffn_stage(moe, cfg, idx_h, wave_rows=2, small_tiles=1, use_row_token=Fal
                         w1p, w3p, w2p, h, y, ysh, ws)
         torch.cuda.synchronize()
     finally:
-        moe.set_option("gemm_wave_rows", 2)
+        moe.set_option("gemm_waves", DEFAULT_WAVES)
+        moe.set_option("gemm_wave_rows", DEFAULT_WAVE_ROWS)
         moe.set_option("small_tiles", 1)
         moe.set_option("y_fp32", 1)
     return y, ysh, perm.cpu().numpy(), off.cpu().numpy(), li
 
 
+DEFAULT_WAVES, DEFAULT_WAVE_ROWS = 4, 2
+
 FFN_CASES = [
-    # name, overrides, skew, wave_rows, small_tiles, row_token
-    ("C1", {}, None, 2, 1, False),
-    ("C1", {}, None, 1, 1, True),
-    ("C1", dict(T=333, H=192, F=320), None, 2, 0, False),        # ragged rows, N not a multiple of the tile
-    ("C4", dict(T=512, H=256, F=192, E=16, top_k=4), None, 2, 1, True),   # shared experts, K-concatenated down proj
-    ("C4", dict(T=300, H=128, F=128, E=16, top_k=4), None, 1, 1, False),
-    ("C5", dict(T=700, H=256, F=128, E=40, top_k=3), "one", 2, 1, False),  # one hot expert, tiny and empty experts
-    ("C1", dict(T=40, H=64, F=64, E=4, top_k=1), None, 2, 1, False),
+    # name, overrides, skew, waves, wave_rows, small_tiles, row_token
+    ("C1", {}, None, 4, 2, 1, False),
+    ("C1", {}, None, 4, 1, 1, True),
+    ("C1", {}, None, 8, 2, 1, True),
+    ("C1", dict(T=333, H=192, F=320), None, 4, 2, 0, False),        # ragged rows, N not a multiple of the tile
+    ("C1", dict(T=333, H=192, F=320), None, 8, 4, 0, False),
+    ("C4", dict(T=512, H=256, F=192, E=16, top_k=4), None, 4, 2, 1, True),   # shared experts, K-concatenated down proj
+    ("C4", dict(T=512, H=256, F=192, E=16, top_k=4), None, 8, 2, 1, True),
+    ("C4", dict(T=300, H=128, F=128, E=16, top_k=4), None, 4, 1, 1, False),
+    ("C4", dict(T=300, H=128, F=128, E=16, top_k=4), None, 8, 4, 1, False),
+    ("C5", dict(T=700, H=256, F=128, E=40, top_k=3), "one", 4, 2, 1, False),  # one hot expert, tiny and empty experts
+    ("C5", dict(T=700, H=256, F=128, E=40, top_k=3), "one", 8, 2, 1, False),
+    ("C5", dict(T=700, H=256, F=128, E=40, top_k=3), "one", 4, 1, 1, False),
+    ("C1", dict(T=40, H=64, F=64, E=4, top_k=1), None, 4, 2, 1, False),
+    ("C1", dict(T=40, H=64, F=64, E=4, top_k=1), None, 8, 4, 1, False),
 ]
 
 
-@pytest.mark.parametrize("name,over,skew,wave_rows,small_tiles,row_token", FFN_CASES)
-def test_grouped_ffn(moe, name, over, skew, wave_rows, small_tiles, row_token):
+@pytest.mark.parametrize("name,over,skew,waves,wave_rows,small_tiles,row_token", FFN_CASES)
+def test_grouped_ffn(moe, name, over, skew, waves, wave_rows, small_tiles, row_token):
     cfg = scaled_config(name, **over) if over else get_config(name)
-    say("grouped_ffn", cfg, skew, wave_rows, small_tiles, row_token)
+    say("grouped_ffn", cfg, skew, waves, wave_rows, small_tiles, row_token)
     rng = np.random.default_rng(cfg.T + cfg.E)
     idx_h = random_routing(rng, cfg.T, cfg.E, cfg.top_k, skew)
-    y, ysh, perm, off, li = run_ffn_stage(moe, cfg, idx_h, wave_rows, small_tiles, row_token)
+    y, ysh, perm, off, li = run_ffn_stage(moe, cfg, idx_h, wave_rows, small_tiles, row_token, waves=waves)
     u = torch_bf16_to_u16
     hw1 = [u(t) for t in li.w1]; hw3 = [u(t) for t in li.w3]; hw2 = [u(t) for t in li.w2]
     hx = u(li.x)
