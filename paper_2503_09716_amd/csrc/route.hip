@@ -28,6 +28,67 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+// Softmax over all experts + top-k for ONE token held by one wavefront: lane l holds the logits
+// of experts l, l+64, ... in v[] (-inf past E).  Max and sum are butterfly reductions; top-k is
+// k rounds of a wave-wide arg-max on the logits (ties -> lower expert id), so rounding in exp /
+// division can never change the selection.
+template <int NV>
+__device__ __forceinline__ void route_finish(const float (&v)[NV], const int lane, const int t, const int E, const int k,
+                                             const int renorm, const float scale, int32_t* __restrict__ idx_out,
+                                             float* __restrict__ w_out, float* __restrict__ logits_out) {
+    float p[NV];
+    float m = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int e = lane + 64 * i;
+        m = fmaxf(m, v[i]);
+        if (logits_out && e < E) logits_out[(size_t)t * E + e] = v[i];
+    }
+    m = wave_max(m);
+    float z = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        p[i] = expf(v[i] - m);  // exp(-inf) = 0 for padded experts
+        z += p[i];
+    }
+    z = wave_sum(z);
+    const float rz = 1.0f / z;
+    float my_w = 0.f;
+    int my_e = 0;
+    unsigned taken = 0;
+    for (int j = 0; j < k; ++j) {
+        // lane-local best among the not-yet-selected (ascending expert id, strict >)
+        float bv = -INFINITY, bp = 0.f;
+        int be = 0x7fffffff;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int e = lane + 64 * i;
+            const bool ok = e < E && !((taken >> i) & 1u);
+            if (ok && (be == 0x7fffffff || v[i] > bv)) { bv = v[i]; be = e; bp = p[i]; }
+        }
+        // wave arg-max, ties -> lower expert id
+#pragma unroll
+        for (int s = 32; s >= 1; s >>= 1) {
+            const float ov = __shfl_xor(bv, s, 64);
+            const int oe = __shfl_xor(be, s, 64);
+            const float op = __shfl_xor(bp, s, 64);
+            if (ov > bv || (ov == bv && oe < be)) { bv = ov; be = oe; bp = op; }
+        }
+        if (lane == j) { my_e = be; my_w = bp * rz; }
+        // retire the winner
+#pragma unroll
+        for (int i = 0; i < NV; ++i)
+            if (lane + 64 * i == be) taken |= 1u << i;
+    }
+    const float wsum = wave_sum(lane < k ? my_w : 0.f);
+    if (lane < k) {
+        float wv = my_w;
+        if (renorm) wv = wv / wsum;
+        idx_out[(size_t)t * k + lane] = my_e;
+        w_out[(size_t)t * k + lane] = wv * scale;
+    }
+}
+
 // TE = experts per thread in phase 1 (thread tid%32 owns experts tid%32 + 32*i, i < TE).
 template <int TE>
 __global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ wg,
@@ -132,58 +193,86 @@ __global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__
     for (int tt = wave; tt < ROUTE_TOK; tt += 4) {
         const int t = t0 + tt;
         if (t >= T) break;  // wave-uniform
-        float v[NV], p[NV];
-        float m = -INFINITY;
+        float v[NV];
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
             const int e = lane + 64 * i;
             v[i] = (e < EP) ? lg[tt * EP + e] : -INFINITY;
-            m = fmaxf(m, v[i]);
-            if (logits_out && e < E) logits_out[(size_t)t * E + e] = v[i];
         }
-        m = wave_max(m);
-        float z = 0.f;
+        route_finish<NV>(v, lane, t, E, k, renorm, scale, idx_out, w_out, logits_out);
+    }
+}
+
+// Few experts (E <= 16): HBM-bound.  One wavefront takes SMALL_TOK tokens; lane l owns the hidden
+// elements h = 512*it + 8*l .. +7, so a wave reads 1 KiB of each token row per step and the
+// matching 8 rows of Wg (8*E contiguous bf16, cache resident).  Per-lane partial sums are
+// combined by a butterfly, after which every lane holds every logit.
+constexpr int SMALL_TOK = 4;
+
+template <int EP, bool EXACT>  // EP: padded expert count (8 or 16); EXACT: E == EP, rows of Wg are 16-byte vectors
+__global__ __launch_bounds__(256) void route_small_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ wg,
+                                                          const float* __restrict__ bias, int T, int H, int E, int k,
+                                                          int renorm, float scale, int32_t* __restrict__ idx_out,
+                                                          float* __restrict__ w_out, float* __restrict__ logits_out) {
+    const int lane = threadIdx.x & 63;
+    const int wave = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int t0 = wave * SMALL_TOK;
+    if (t0 >= T) return;
+    float acc[SMALL_TOK][EP];
 #pragma unroll
-        for (int i = 0; i < NV; ++i) {
-            p[i] = expf(v[i] - m);  // exp(-inf) = 0 for padded experts
-            z += p[i];
+    for (int a = 0; a < SMALL_TOK; ++a)
+#pragma unroll
+        for (int e = 0; e < EP; ++e) acc[a][e] = 0.f;
+    for (int h0 = lane * 8; h0 < H; h0 += 512) {
+        uint4 xv[SMALL_TOK];
+#pragma unroll
+        for (int a = 0; a < SMALL_TOK; ++a) {
+            const int t = min(t0 + a, T - 1);
+            xv[a] = *reinterpret_cast<const uint4*>(x + (size_t)t * H + h0);
         }
-        z = wave_sum(z);
-        const float rz = 1.0f / z;
-        float my_w = 0.f;
-        int my_e = 0;
-        unsigned taken = 0;
-        for (int j = 0; j < k; ++j) {
-            // lane-local best among the not-yet-selected (ascending expert id, strict >)
-            float bv = -INFINITY, bp = 0.f;
-            int be = 0x7fffffff;
 #pragma unroll
-            for (int i = 0; i < NV; ++i) {
-                const int e = lane + 64 * i;
-                const bool ok = e < E && !((taken >> i) & 1u);
-                if (ok && (be == 0x7fffffff || v[i] > bv)) { bv = v[i]; be = e; bp = p[i]; }
+        for (int hh = 0; hh < 8; ++hh) {
+            float xa[SMALL_TOK];
+#pragma unroll
+            for (int a = 0; a < SMALL_TOK; ++a) {
+                const uint32_t u = (&xv[a].x)[hh >> 1];
+                xa[a] = (hh & 1) ? __uint_as_float(u & 0xffff0000u) : __uint_as_float(u << 16);
             }
-            // wave arg-max, ties -> lower expert id
+            const uint16_t* wr = wg + (size_t)(h0 + hh) * E;
+            float wv[EP];
+            if (EXACT) {
 #pragma unroll
-            for (int s = 32; s >= 1; s >>= 1) {
-                const float ov = __shfl_xor(bv, s, 64);
-                const int oe = __shfl_xor(be, s, 64);
-                const float op = __shfl_xor(bp, s, 64);
-                if (ov > bv || (ov == bv && oe < be)) { bv = ov; be = oe; bp = op; }
+                for (int c = 0; c < EP / 8; ++c) {
+                    const uint4 q = reinterpret_cast<const uint4*>(wr)[c];
+                    const uint32_t u[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        wv[c * 8 + 2 * i] = __uint_as_float(u[i] << 16);
+                        wv[c * 8 + 2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < EP; ++e) wv[e] = e < E ? __uint_as_float((uint32_t)wr[e] << 16) : 0.f;
             }
-            if (lane == j) { my_e = be; my_w = bp * rz; }
-            // retire the winner
 #pragma unroll
-            for (int i = 0; i < NV; ++i)
-                if (lane + 64 * i == be) taken |= 1u << i;
+            for (int e = 0; e < EP; ++e)
+#pragma unroll
+                for (int a = 0; a < SMALL_TOK; ++a) acc[a][e] = fmaf(xa[a], wv[e], acc[a][e]);
         }
-        float wsum = wave_sum(lane < k ? my_w : 0.f);
-        if (lane < k) {
-            float wv = my_w;
-            if (renorm) wv = wv / wsum;
-            idx_out[(size_t)t * k + lane] = my_e;
-            w_out[(size_t)t * k + lane] = wv * scale;
+    }
+#pragma unroll
+    for (int a = 0; a < SMALL_TOK; ++a) {
+        const int t = t0 + a;
+        if (t >= T) break;  // wave-uniform
+        float mine = -INFINITY;
+#pragma unroll
+        for (int e = 0; e < EP; ++e) {
+            const float tot = wave_sum(acc[a][e]);
+            if (lane == e && e < E) mine = tot + (bias ? bias[e] : 0.f);
         }
+        const float v[1] = {mine};
+        route_finish<1>(v, lane, t, E, k, renorm, scale, idx_out, w_out, logits_out);
     }
 }
 
@@ -191,6 +280,18 @@ __global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__
 
 hipError_t launch_route(const moe_shape& s, const void* x, const void* wg, const float* bias, int32_t* idx,
                         float* w, float* logits, hipStream_t st) {
+    if (s.E <= 16) {
+        const dim3 g((s.T + 4 * SMALL_TOK - 1) / (4 * SMALL_TOK)), b(256);
+#define ROUTE_SMALL(EP_, EX_)                                                                                  \
+    hipLaunchKernelGGL((route_small_kernel<EP_, EX_>), g, b, 0, st, (const uint16_t*)x, (const uint16_t*)wg, bias, \
+                       s.T, s.H, s.E, s.top_k, s.renormalize, s.routed_scale, idx, w, logits)
+        if (s.E == 8) ROUTE_SMALL(8, true);
+        else if (s.E < 8) ROUTE_SMALL(8, false);
+        else if (s.E == 16) ROUTE_SMALL(16, true);
+        else ROUTE_SMALL(16, false);
+#undef ROUTE_SMALL
+        return hipGetLastError();
+    }
     const dim3 grid((s.T + ROUTE_TOK - 1) / ROUTE_TOK), block(256);
     const int te = (s.E + 31) / 32;
 #define ROUTE_CASE(N)                                                                                         \

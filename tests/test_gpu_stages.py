@@ -33,6 +33,10 @@ ROUTE_CASES = [
     ("C1", dict(T=1, H=64)),
     ("C1", dict(T=33, H=64, E=8, top_k=8)),      # k = E
     ("C4", dict(T=65, H=128, E=200, top_k=13)),   # E not a multiple of 32, odd k
+    ("C1", dict(T=101, H=128, E=5, top_k=2)),     # few experts, not a vector width
+    ("C1", dict(T=70, H=192, E=16, top_k=4)),
+    ("C3", dict(T=50, H=64, E=12, top_k=3)),
+    ("C1", dict(T=9, H=1088, E=1, top_k=1)),
 ]
 
 
