@@ -93,6 +93,8 @@ size_t moe_workspace_bytes(const moe_shape* shape);
  *   "gemm_group_m"    1..64   m-tiles swept together along n (L2 reuse of weight panels)
  *   "xcd_remap"       0 | 1   give each XCD runs of consecutive tiles
  *   "small_tiles"     0 | 1   use 128/64/32-row tiles for the ragged tail of an expert
+ *   "gemm_tile_rows_up" / "gemm_tile_rows_down"  0 | 128 | 256   rows per m-tile of the gate/up and
+ *                             the down GEMM; 0 (default) picks per launch from the tile count
  *   "probe_k_resident" 0 | 1  timing probe only: the GEMMs re-read their first K tile at every K step
  *                             (operands stay cache resident, RESULTS ARE MEANINGLESS); default 0
  *   "y_fp32"          0 | 1   dtype of y_perm / y_shared: 1 (default) fp32, 0 bf16.  bf16 halves the

@@ -26,7 +26,7 @@ struct ProfRec {
 struct moe_ctx {
     int device = 0;
     char err[512] = {0};
-    GemmConfig gemm{2, 4, 8, 1, 1, 0};
+    GemmConfig gemm{2, 4, 8, 1, 1, 0, 0, 0};
     bool y_fp32 = true;    // dtype of y_perm / y_shared
     bool out_fp32 = false; // dtype of the layer output
     // Ring of device pointer tables [3][MAX_GROUPS] (W1p, W3p, W2p), each with a pinned host
@@ -86,7 +86,7 @@ inline size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
 // Workspace layout: fixed order, every region 256-byte aligned.
 struct Layout {
-    size_t topk_idx, topk_w, offsets, perm, inv_perm, row_token, chunk_counts, plan, descs, h, y_perm, y_shared, total;
+    size_t topk_idx, topk_w, offsets, perm, inv_perm, row_token, chunk_counts, plan, descs_up, descs_down, h, y_perm, y_shared, total;
 };
 
 Layout make_layout(const moe_shape& s) {
@@ -102,7 +102,8 @@ Layout make_layout(const moe_shape& s) {
     L.row_token = take(R * 4);
     L.chunk_counts = take((size_t)permute_chunks(s) * s.E * 4);
     L.plan = take(sizeof(PlanHeader));
-    L.descs = take((size_t)max_mtiles(s) * sizeof(TileDesc));
+    L.descs_up = take((size_t)max_mtiles(s, 128) * sizeof(TileDesc));
+    L.descs_down = take((size_t)max_mtiles(s, 128) * sizeof(TileDesc));
     L.h = take((R + Rs) * s.F * 2);
     L.y_perm = take(R * s.H * 4);  // sized for fp32 y
     L.y_shared = take(Rs ? (size_t)s.T * s.H * 4 : 0);
@@ -183,29 +184,49 @@ moe_status weight_table(moe_ctx* c, int n, const void* const* w1, const void* co
     return MOE_OK;
 }
 
+// Rows per m-tile for one GEMM.  Tiles of 256 rows are the efficient shape (measured: the
+// 128-row shape runs at ~0.75 of their rate); 128 rows only win when a launch has so few
+// 256-row tiles that most CUs would idle in its last round.
+int pick_tile_rows(const moe_shape& s, int n_tiles, int nseg) {
+    const double R = (double)s.T * s.top_k;
+    double best = 0;
+    int best_tm = 256;
+    for (int tm : {256, 128}) {
+        const double tiles = (R / tm + 0.5 * s.E + (double)nseg * ((s.T + tm - 1) / tm)) * n_tiles;
+        const double rounds = (double)(int64_t)((tiles + 255) / 256);
+        const double cost = rounds * tm * (tm == 128 ? 1.35 : 1.0);
+        if (best == 0 || cost < best) { best = cost; best_tm = tm; }
+    }
+    return best_tm;
+}
+
 moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int32_t* row_token, const void* x,
                    const int32_t* offsets, void** tab, char* ws, void* h, void* y_perm, void* y_shared,
                    hipStream_t st) {
     const Layout L = make_layout(s);
     PlanHeader* plan = (PlanHeader*)(ws + L.plan);
-    TileDesc* descs = (TileDesc*)(ws + L.descs);
+    TileDesc* descs_up = (TileDesc*)(ws + L.descs_up);
+    TileDesc* descs_down = (TileDesc*)(ws + L.descs_down);
     const size_t R = (size_t)s.T * s.top_k;
+    const int nt_up = (s.F + 127) / 128, nt_down = (s.H + 255) / 256;
+    const int tm_up = c->gemm.tile_rows_up ? c->gemm.tile_rows_up : pick_tile_rows(s, nt_up, s.num_shared);
+    const int tm_down = c->gemm.tile_rows_down ? c->gemm.tile_rows_down : pick_tile_rows(s, nt_down, s.num_shared ? 1 : 0);
     {
         StageTimer tm(c, st, MOE_STAGE_PLAN);
-        HIP_TRY(c, launch_ffn_plan(s, offsets, plan, descs, c->gemm.small_tiles, c->gemm.wave_rows, st));
+        HIP_TRY(c, launch_ffn_plan(s, offsets, tm_up, tm_down, plan, descs_up, descs_down, st));
     }
     GemmArgs a;
     memset(&a, 0, sizeof(a));
-    a.descs = descs;
     a.plan = plan;
     a.T = s.T;
-    a.max_mtiles = (int)max_mtiles(s);
     a.group_m = c->gemm.group_m;
     a.xcd_remap = c->gemm.xcd_remap;
     a.small_tiles = c->gemm.small_tiles;
     a.out_fp32 = 0;
     a.k_step_bytes = c->gemm.probe_k_resident ? 0 : 64;
     // GEMM 1: [rows, H] x W1p/W3p [F, H] -> h [rows, F]
+    a.descs = descs_up;
+    a.max_mtiles = (int)max_mtiles(s, tm_up);
     a.a_routed = (const char*)(row_token ? x : x_perm);
     a.a_shared = (const char*)x;
     a.row_token = row_token;
@@ -216,12 +237,14 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     a.K = s.H;
     a.N = s.F;
     a.nseg_shared = 1;
-    a.n_tiles = (s.F + 127) / 128;
+    a.n_tiles = nt_up;
     {
         StageTimer tm(c, st, MOE_STAGE_FFN_GATE_UP);
         HIP_TRY(c, launch_ffn_gemm(true, a, c->gemm, st));
     }
     // GEMM 2: h [rows, F] x W2p [H, F] -> y [rows, H]
+    a.descs = descs_down;
+    a.max_mtiles = (int)max_mtiles(s, tm_down);
     a.a_routed = (const char*)h;
     a.a_shared = (const char*)h + R * s.F * 2;
     a.row_token = nullptr;
@@ -233,7 +256,7 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     a.N = s.H;
     a.nseg_shared = s.num_shared > 0 ? s.num_shared : 1;
     a.out_fp32 = c->y_fp32 ? 1 : 0;
-    a.n_tiles = (s.H + 255) / 256;
+    a.n_tiles = nt_down;
     {
         StageTimer tm(c, st, MOE_STAGE_FFN_DOWN);
         HIP_TRY(c, launch_ffn_gemm(false, a, c->gemm, st));
@@ -293,6 +316,8 @@ moe_status moe_set_option(moe_ctx* c, const char* key, int32_t v) {
     if (!strcmp(key, "gemm_group_m") && v >= 1 && v <= 64) { c->gemm.group_m = v; return MOE_OK; }
     if (!strcmp(key, "xcd_remap") && (v == 0 || v == 1)) { c->gemm.xcd_remap = v; return MOE_OK; }
     if (!strcmp(key, "small_tiles") && (v == 0 || v == 1)) { c->gemm.small_tiles = v; return MOE_OK; }
+    if (!strcmp(key, "gemm_tile_rows_up") && (v == 0 || v == 128 || v == 256)) { c->gemm.tile_rows_up = v; return MOE_OK; }
+    if (!strcmp(key, "gemm_tile_rows_down") && (v == 0 || v == 128 || v == 256)) { c->gemm.tile_rows_down = v; return MOE_OK; }
     if (!strcmp(key, "probe_k_resident") && (v == 0 || v == 1)) { c->gemm.probe_k_resident = v; return MOE_OK; }
     if (!strcmp(key, "y_fp32") && (v == 0 || v == 1)) { c->y_fp32 = v != 0; return MOE_OK; }
     if (!strcmp(key, "out_fp32") && (v == 0 || v == 1)) { c->out_fp32 = v != 0; return MOE_OK; }

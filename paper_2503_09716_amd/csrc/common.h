@@ -25,8 +25,8 @@ struct TileDesc {
 };
 
 struct PlanHeader {
-    int32_t n_gate_up;  // tiles of GEMM 1 (routed + every shared expert)
-    int32_t n_down;     // tiles of GEMM 2 (routed + shared expert 0; shared experts are K-concatenated)
+    int32_t n_gate_up;  // m-tiles of GEMM 1 (routed + every shared expert)
+    int32_t n_down;     // m-tiles of GEMM 2 (routed + shared expert 0; shared experts are K-concatenated)
     int32_t pad[2];
 };
 
@@ -58,13 +58,15 @@ struct GemmConfig {
     int group_m;
     int xcd_remap;
     int small_tiles;
+    int tile_rows_up;      // rows per m-tile of the gate/up GEMM: 0 = choose per launch, else 128 or 256
+    int tile_rows_down;    // same for the down GEMM
     int probe_k_resident;  // timing probe: every K step re-reads the first tile (results are meaningless)
 };
 
-// Upper bound on the number of m-tiles for any routing outcome.
-inline int64_t max_mtiles(const moe_shape& s) {
+// Upper bound on the number of m-tiles of `tm` rows for any routing outcome.
+inline int64_t max_mtiles(const moe_shape& s, int tm) {
     const int64_t R = (int64_t)s.T * s.top_k;
-    return R / 256 + s.E + (int64_t)s.num_shared * ((s.T + 255) / 256);
+    return R / tm + s.E + (int64_t)s.num_shared * ((s.T + tm - 1) / tm);
 }
 
 // ---- launchers (each only enqueues on `st`; returns the launch status) ----
@@ -78,8 +80,8 @@ hipError_t launch_permute_index(const moe_shape& s, const int32_t* idx, int32_t*
 hipError_t launch_permute_gather(const moe_shape& s, const void* x, const int32_t* perm, void* x_perm,
                                  hipStream_t st);
 
-hipError_t launch_ffn_plan(const moe_shape& s, const int32_t* offsets, PlanHeader* plan, TileDesc* descs,
-                           int small_tiles, int wave_rows, hipStream_t st);
+hipError_t launch_ffn_plan(const moe_shape& s, const int32_t* offsets, int tm_up, int tm_down, PlanHeader* plan,
+                           TileDesc* descs_up, TileDesc* descs_down, hipStream_t st);
 hipError_t launch_ffn_gemm(bool gated, const GemmArgs& a, const GemmConfig& cfg, hipStream_t st);
 hipError_t ffn_gemm_init();  // one-time function attributes (dynamic LDS size)
 

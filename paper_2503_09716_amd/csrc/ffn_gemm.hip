@@ -296,8 +296,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
                 for (int q = 0; q < 8; ++q) {
                     const float g0 = acc[j][i][q], u0 = acc[j + TJH][i][q];
                     const float g1 = acc[j][i][q + 8], u1 = acc[j + TJH][i][q + 8];
-                    o0[q] = (__bf16)((g0 / (1.0f + __expf(-g0))) * u0);
-                    o1[q] = (__bf16)((g1 / (1.0f + __expf(-g1))) * u1);
+                    // silu(g) * u with the hardware reciprocal (1 ulp): far below the bf16 rounding of h
+                    o0[q] = (__bf16)(g0 * __builtin_amdgcn_rcpf(1.0f + __expf(-g0)) * u0);
+                    o1[q] = (__bf16)(g1 * __builtin_amdgcn_rcpf(1.0f + __expf(-g1)) * u1);
                 }
                 *reinterpret_cast<bf16x8*>(orow + (size_t)col * 2) = o0;
                 *reinterpret_cast<bf16x8*>(orow + (size_t)col * 2 + 16) = o1;
@@ -403,18 +404,18 @@ __global__ __launch_bounds__(512, 2) void ffn_gemm_kernel8(const GemmArgs p) {
     }
 }
 
-// Builds the m-tile list from expert_offsets.  Order: shared expert 0, routed experts, shared
-// experts 1.. (GEMM 2 takes the first two parts: shared experts are concatenated along K there).
-// A group of n rows becomes floor(n/256) full tiles plus one tail tile (small_tiles) or
-// ceil(n/256) tiles of 256 rows (the kernel still picks a short variant for a short tail).
+// Builds the two m-tile lists (gate/up GEMM with tiles of tm_up rows, down GEMM with tm_down rows)
+// from expert_offsets.  Order: shared expert 0, routed experts, shared experts 1.. (the down
+// GEMM takes the first two parts only: shared experts are concatenated along K there).
+// A group of n rows becomes ceil(n/tm) tiles; the kernel runs a short variant on a short tail.
 __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict__ offsets, int T, int E, int Ns,
-                                                       PlanHeader* __restrict__ plan, TileDesc* __restrict__ descs) {
+                                                       int tm_up, int tm_down, PlanHeader* __restrict__ plan,
+                                                       TileDesc* __restrict__ descs_up, TileDesc* __restrict__ descs_down) {
     __shared__ int first[256];
     const int tid = threadIdx.x;
-    const int shared_tiles = (T + 255) / 256;
     // group order: g = 0 -> shared 0 (if any), then routed 0..E-1, then shared 1..Ns-1
     const int ngroups = E + Ns;
-    int ntiles = 0, row_begin = 0, rows = 0, group = 0, srow = -1;
+    int row_begin = 0, rows = 0, group = 0, srow = -1;
     if (tid < ngroups) {
         int pos = tid;
         if (Ns > 0 && pos == 0) { group = E; rows = T; row_begin = 0; srow = 0; }
@@ -423,34 +424,36 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
             if (pos < E) { group = pos; row_begin = offsets[pos]; rows = offsets[pos + 1] - row_begin; srow = -1; }
             else { const int s = pos - E + 1; group = E + s; rows = T; row_begin = 0; srow = s * T; }
         }
-        ntiles = (rows + 255) / 256;
     }
-    first[tid] = ntiles;
-    __syncthreads();
-    if (tid == 0) {
-        int run = 0, down = 0;
-        for (int i = 0; i < ngroups && i < 256; ++i) {
-            const int v = first[i];
-            first[i] = run;
-            run += v;
-            if (i == (Ns > 0 ? E : E - 1)) down = run;  // end of (shared 0 +) routed part
+    for (int which = 0; which < 2; ++which) {
+        const int tm = which == 0 ? tm_up : tm_down;
+        TileDesc* descs = which == 0 ? descs_up : descs_down;
+        const int last = which == 0 ? ngroups - 1 : (Ns > 0 ? E : E - 1);  // last group of this list
+        const int ntiles = (tid <= last) ? (rows + tm - 1) / tm : 0;
+        __syncthreads();
+        first[tid] = ntiles;
+        __syncthreads();
+        if (tid == 0) {
+            int run = 0;
+            for (int i = 0; i <= last; ++i) {
+                const int v = first[i];
+                first[i] = run;
+                run += v;
+            }
+            if (which == 0) plan->n_gate_up = run;
+            else plan->n_down = run;
         }
-        if (Ns == 0) down = run;
-        plan->n_gate_up = run;
-        plan->n_down = down;
-        plan->pad[0] = shared_tiles;
-        plan->pad[1] = 0;
-    }
-    __syncthreads();
-    if (tid < ngroups) {
-        const int base = first[tid];
-        for (int i = 0; i < ntiles; ++i) {
-            TileDesc d;
-            d.group = group;
-            d.row0 = row_begin + i * 256;
-            d.nrows = min(256, rows - i * 256);
-            d.srow = srow;
-            descs[base + i] = d;
+        __syncthreads();
+        if (tid <= last) {
+            const int base = first[tid];
+            for (int i = 0; i < ntiles; ++i) {
+                TileDesc d;
+                d.group = group;
+                d.row0 = row_begin + i * tm;
+                d.nrows = min(tm, rows - i * tm);
+                d.srow = srow;
+                descs[base + i] = d;
+            }
         }
     }
 }
@@ -475,11 +478,10 @@ hipError_t ffn_gemm_init() {
     return hipSuccess;
 }
 
-hipError_t launch_ffn_plan(const moe_shape& s, const int32_t* offsets, PlanHeader* plan, TileDesc* descs,
-                           int small_tiles, int wave_rows, hipStream_t st) {
-    (void)small_tiles;
-    (void)wave_rows;
-    hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(256), 0, st, offsets, s.T, s.E, s.num_shared, plan, descs);
+hipError_t launch_ffn_plan(const moe_shape& s, const int32_t* offsets, int tm_up, int tm_down, PlanHeader* plan,
+                           TileDesc* descs_up, TileDesc* descs_down, hipStream_t st) {
+    hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(256), 0, st, offsets, s.T, s.E, s.num_shared, tm_up, tm_down,
+                       plan, descs_up, descs_down);
     return hipGetLastError();
 }
 
