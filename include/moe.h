@@ -24,10 +24,13 @@
  *  - Expert weight tables are HOST arrays of DEVICE pointers, read when the call is made,
  *    so that a weight streamer may repoint them between calls (sequential execution of
  *    experts with prefetched weights, Sec. 4.2).
- *  - Weight layout on the hot path is the PACKED one: every matrix is stored with the
- *    contraction dimension contiguous, i.e. W1p_e, W3p_e are [F,H] and W2p_e is [H,F]
- *    (the transposes of the logical [H,F] / [F,H] matrices).  moe_pack_weight converts a
- *    logical matrix once; weights are static, so this is not part of the timed path.
+ *  - Weight layout on the hot path is the PACKED one produced by moe_pack_weight from the
+ *    logical [H,F] / [F,H] matrices (same number of bytes): the transposed matrix W[n][k]
+ *    (k = contraction index) is cut into blocks of 16 rows x 32 k = 1 KiB, blocks ordered
+ *    [N/16][K/32]; inside a block, row r (0..15) occupies bytes 64r..64r+63 and its 16-byte
+ *    piece c (k = 8c..8c+7) sits at slot c ^ ((r/4)&3); inside every aligned 32-row block the
+ *    rows are permuted: packed row 32b+rho holds logical row 32b + ((rho/4)&1)*16 +
+ *    (rho/8)*4 + (rho&3).  Weights are static, so packing is not part of the timed path.
  *  - Limits: H % 64 == 0, F % 64 == 0, 1 <= top_k <= E <= 256, top_k <= 64,
  *    0 <= num_shared <= 8, every matrix below 4 GiB.  Other shapes: MOE_E_UNSUPPORTED.
  */
@@ -86,6 +89,11 @@ const char* moe_last_error(const moe_ctx* ctx);
  * Returns 0 for an invalid shape. */
 size_t moe_workspace_bytes(const moe_shape* shape);
 
+/* Bytes of the h scratch that moe_grouped_ffn needs: (roundup16(T*k) + num_shared *
+ * roundup16(T)) rows of F bf16 (h is kept in 16-row x 32-column blocks, and the routed rows
+ * and each shared expert's rows start on a block boundary).  0 for an invalid shape. */
+size_t moe_h_scratch_bytes(const moe_shape* shape);
+
 /* Tuning knobs (host call).  Unknown key or out-of-range value: MOE_E_ARG.
  *   "gemm_waves"      4 | 8   wavefronts per GEMM workgroup (one or two per SIMD)
  *   "gemm_wave_rows"  1|2|4   rows of the wave grid (rows x waves/rows): 1 or 2 with 4 waves (4 rows
@@ -104,8 +112,9 @@ size_t moe_workspace_bytes(const moe_shape* shape);
  *                             0 (default) bf16 = round-to-nearest-even of the fp32 sum, 1 fp32 */
 moe_status moe_set_option(moe_ctx* ctx, const char* key, int32_t value);
 
-/* One-time weight packing: w_logical [rows, cols] bf16 (device) -> w_packed [cols, rows]
- * bf16 (device, distinct buffer).  rows, cols multiples of 8. */
+/* One-time weight packing: w_logical [rows, cols] bf16 (device; rows = contraction dimension)
+ * -> w_packed, rows*cols bf16 in the packed layout described above (device, distinct buffer).
+ * rows, cols multiples of 32. */
 moe_status moe_pack_weight(moe_ctx* ctx, const void* w_logical, int32_t rows, int32_t cols,
                            void* w_packed, void* hip_stream);
 
@@ -143,8 +152,9 @@ moe_status moe_permute(moe_ctx* ctx, const moe_shape* shape, const void* x_bf16,
  *   row_token_or_null [T*k] int32 device: row r of the expert input is x[row_token[r],:]
  *   x_bf16 [T,H] device in: needed when num_shared > 0 or row_token is given, else may be NULL
  *   expert_offsets [E+1] int32 device in
- *   w1p, w3p, w2p: host arrays of E+num_shared device pointers, packed layout (see above)
- *   h_scratch_bf16 [(T*k + T*num_shared), F] device scratch
+ *   w1p, w3p, w2p: host arrays of E+num_shared device pointers; w1p[e] / w3p[e] = moe_pack_weight of
+ *   the logical [H,F] gate / up matrix, w2p[e] = moe_pack_weight of the logical [F,H] down matrix
+ *   h_scratch_bf16: device scratch of moe_h_scratch_bytes(shape) bytes
  *   y_perm [T*k,H] device out; y_shared [T,H] device out (NULL iff num_shared == 0); both fp32,
  *   or bf16 under option "y_fp32" = 0
  *   workspace: device, at least moe_workspace_bytes(shape). */

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(HERE, "libmoe_mi355.so")
 STAGES = ["route", "permute_index", "permute_gather", "plan", "ffn_gate_up", "ffn_down", "combine"]
 
 EXPORTS = [
-    "moe_create", "moe_destroy", "moe_last_error", "moe_workspace_bytes", "moe_set_option", "moe_pack_weight",
+    "moe_create", "moe_destroy", "moe_last_error", "moe_workspace_bytes", "moe_h_scratch_bytes", "moe_set_option", "moe_pack_weight",
     "moe_route", "moe_permute", "moe_grouped_ffn", "moe_combine", "moe_layer", "moe_layer_views",
     "moe_profile_enable", "moe_profile_read",
 ]
@@ -57,6 +57,8 @@ def load_library():
     lib.moe_last_error.restype = C.c_char_p
     lib.moe_workspace_bytes.argtypes = [sp]
     lib.moe_workspace_bytes.restype = C.c_size_t
+    lib.moe_h_scratch_bytes.argtypes = [sp]
+    lib.moe_h_scratch_bytes.restype = C.c_size_t
     lib.moe_set_option.argtypes = [C.c_void_p, C.c_char_p, C.c_int32]
     lib.moe_pack_weight.argtypes = [C.c_void_p, vp, C.c_int32, C.c_int32, vp, vp]
     lib.moe_route.argtypes = [C.c_void_p, sp, vp, vp, f32p, i32p, f32p, f32p, vp]
@@ -69,7 +71,7 @@ def load_library():
     lib.moe_profile_enable.argtypes = [C.c_void_p, C.c_int32]
     lib.moe_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
     for name in EXPORTS:
-        if name not in ("moe_destroy", "moe_last_error", "moe_workspace_bytes"):
+        if name not in ("moe_destroy", "moe_last_error", "moe_workspace_bytes", "moe_h_scratch_bytes"):
             getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -86,6 +88,10 @@ def shape_of(cfg) -> MoeShape:
 
 def workspace_bytes(shape: MoeShape) -> int:
     return int(load_library().moe_workspace_bytes(C.byref(shape)))
+
+
+def h_scratch_bytes(shape: MoeShape) -> int:
+    return int(load_library().moe_h_scratch_bytes(C.byref(shape)))
 
 
 def _ptr(t: Optional[torch.Tensor]):
@@ -142,9 +148,13 @@ class Moe:
         return torch.empty(n, dtype=torch.uint8, device="cuda:%d" % self.device)
 
     # ---- one-time weight packing -------------------------------------------------------
+    def new_h_scratch(self, shape: MoeShape) -> torch.Tensor:
+        return torch.empty(h_scratch_bytes(shape), dtype=torch.uint8, device="cuda:%d" % self.device)
+
     def pack_weight(self, w: torch.Tensor) -> torch.Tensor:
+        """Logical [K, N] weight -> packed form (opaque 1-D bf16 tensor of K*N elements)."""
         rows, cols = w.shape
-        out = torch.empty((cols, rows), dtype=torch.bfloat16, device=w.device)
+        out = torch.empty(rows * cols, dtype=torch.bfloat16, device=w.device)
         self._check(self.lib.moe_pack_weight(self.h, _ptr(w), rows, cols, _ptr(out), _stream()))
         return out
 

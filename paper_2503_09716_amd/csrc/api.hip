@@ -76,7 +76,7 @@ const char* shape_problem(const moe_shape* s, moe_status* st) {
     const int64_t lim = (int64_t)1 << 32;
     const int64_t R = (int64_t)s->T * s->top_k, Rs = (int64_t)s->T * s->num_shared;
     if (R >= ((int64_t)1 << 31) / 2) return "T * top_k too large";
-    if (R * s->H * 2 >= lim || (R + Rs) * s->F * 2 >= lim || (int64_t)s->H * s->F * 2 >= lim)
+    if (R * s->H * 2 >= lim || (R + Rs + 16 * (1 + s->num_shared)) * s->F * 2 >= lim || (int64_t)s->H * s->F * 2 >= lim)
         return "a matrix reaches 4 GiB";
     *st = MOE_OK;
     return nullptr;
@@ -104,7 +104,7 @@ Layout make_layout(const moe_shape& s) {
     L.plan = take(sizeof(PlanHeader));
     L.descs_up = take((size_t)max_mtiles(s, 128) * sizeof(TileDesc));
     L.descs_down = take((size_t)max_mtiles(s, 128) * sizeof(TileDesc));
-    L.h = take((R + Rs) * s.F * 2);
+    L.h = take((size_t)h_rows(s) * s.F * 2);
     L.y_perm = take(R * s.H * 4);  // sized for fp32 y
     L.y_shared = take(Rs ? (size_t)s.T * s.H * 4 : 0);
     L.total = o;
@@ -207,7 +207,7 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     PlanHeader* plan = (PlanHeader*)(ws + L.plan);
     TileDesc* descs_up = (TileDesc*)(ws + L.descs_up);
     TileDesc* descs_down = (TileDesc*)(ws + L.descs_down);
-    const size_t R = (size_t)s.T * s.top_k;
+    const size_t Rpad = ((size_t)s.T * s.top_k + 15) & ~(size_t)15;   // shared experts' rows of h start block-aligned
     const int nt_up = (s.F + 127) / 128, nt_down = (s.H + 255) / 256;
     const int tm_up = c->gemm.tile_rows_up ? c->gemm.tile_rows_up : pick_tile_rows(s, nt_up, s.num_shared);
     const int tm_down = c->gemm.tile_rows_down ? c->gemm.tile_rows_down : pick_tile_rows(s, nt_down, s.num_shared ? 1 : 0);
@@ -223,7 +223,8 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     a.xcd_remap = c->gemm.xcd_remap;
     a.small_tiles = c->gemm.small_tiles;
     a.out_fp32 = 0;
-    a.k_step_bytes = c->gemm.probe_k_resident ? 0 : 64;
+    a.k_step_on = c->gemm.probe_k_resident ? 0 : 1;
+    a.t_pad = (s.T + 15) & ~15;
     // GEMM 1: [rows, H] x W1p/W3p [F, H] -> h [rows, F]
     a.descs = descs_up;
     a.max_mtiles = (int)max_mtiles(s, tm_up);
@@ -233,7 +234,7 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     a.w_a = (const void* const*)tab;
     a.w_b = (const void* const*)(tab + MAX_GROUPS);
     a.out_routed = (char*)h;
-    a.out_shared = (char*)h + R * s.F * 2;
+    a.out_shared = (char*)h + Rpad * s.F * 2;
     a.K = s.H;
     a.N = s.F;
     a.nseg_shared = 1;
@@ -246,7 +247,7 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     a.descs = descs_down;
     a.max_mtiles = (int)max_mtiles(s, tm_down);
     a.a_routed = (const char*)h;
-    a.a_shared = (const char*)h + R * s.F * 2;
+    a.a_shared = (const char*)h + Rpad * s.F * 2;
     a.row_token = nullptr;
     a.w_a = (const void* const*)(tab + 2 * MAX_GROUPS);
     a.w_b = nullptr;
@@ -302,6 +303,12 @@ void moe_destroy(moe_ctx* c) {
 
 const char* moe_last_error(const moe_ctx* c) { return c ? c->err : "context is NULL"; }
 
+size_t moe_h_scratch_bytes(const moe_shape* s) {
+    moe_status st;
+    if (shape_problem(s, &st)) return 0;
+    return (size_t)h_rows(*s) * s->F * 2;
+}
+
 size_t moe_workspace_bytes(const moe_shape* s) {
     moe_status st;
     if (shape_problem(s, &st)) return 0;
@@ -328,10 +335,10 @@ moe_status moe_pack_weight(moe_ctx* c, const void* w, int32_t rows, int32_t cols
     if (!c) return MOE_E_ARG;
     c->err[0] = 0;
     if (!w || !packed || w == packed) return fail(c, MOE_E_ARG, "pack: NULL or aliased buffers");
-    if (rows < 8 || cols < 8 || rows % 8 || cols % 8) return fail(c, MOE_E_ARG, "pack: rows, cols must be positive multiples of 8");
+    if (rows < 32 || cols < 32 || rows % 32 || cols % 32) return fail(c, MOE_E_ARG, "pack: rows, cols must be positive multiples of 32");
     if ((int64_t)rows * cols * 2 >= ((int64_t)1 << 32)) return fail(c, MOE_E_UNSUPPORTED, "pack: matrix reaches 4 GiB");
     HIP_TRY(c, hipSetDevice(c->device));
-    HIP_TRY(c, launch_transpose(w, rows, cols, packed, (hipStream_t)stream));
+    HIP_TRY(c, launch_pack_weight(w, rows, cols, packed, (hipStream_t)stream));
     return MOE_OK;
 }
 

@@ -1,4 +1,4 @@
-// Weighted combine back to token order, and the one-time weight transpose.
+// Weighted combine back to token order, and the one-time weight packing.
 // (Sec. 2: the layer output is the weighted sum of the k experts' outputs, plus the shared
 // expert every token passes through.)
 //
@@ -60,20 +60,41 @@ __global__ __launch_bounds__(256) void combine_kernel(const char* __restrict__ y
     }
 }
 
-// out[c][r] = in[r][c] for a [rows, cols] bf16 matrix, 64x64 tiles through LDS.
-__global__ __launch_bounds__(256) void transpose_kernel(const uint16_t* __restrict__ in, int rows, int cols,
-                                                        uint16_t* __restrict__ out) {
-    __shared__ uint16_t tile[64][66];
-    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int i = ty; i < 64; i += 4) {
-        const int r = r0 + i, c = c0 + tx;
-        tile[i][tx] = (r < rows && c < cols) ? in[(size_t)r * cols + c] : (uint16_t)0;
+// One-time weight packing.  in: logical [K, N] bf16 row-major (K = contraction dimension).
+// out: the tiled layout the GEMM loads, i.e. the matrix W[n][k] = in[k][n] cut into blocks of
+// 16 rows x 32 k (1 KiB), blocks ordered [N/16][K/32]; inside a block, row r (0..15) occupies
+// bytes r*64..r*64+63 and its 16-byte piece c (k = 8c..8c+7) sits at slot c ^ ((r/4)&3).
+// Rows are permuted inside every aligned 32-row block: packed row 32b + rho holds logical row
+// 32b + ((rho/4)&1)*16 + (rho/8)*4 + (rho&3), the order in which the MFMA accumulator
+// registers of a lane enumerate output columns.
+// One workgroup transposes a 32 k x 32 n patch through LDS.
+__global__ __launch_bounds__(256) void pack_weight_kernel(const uint16_t* __restrict__ in, int K, int N,
+                                                          uint16_t* __restrict__ out) {
+    __shared__ uint16_t patch[32][34];
+    const int kt = blockIdx.x, b = blockIdx.y;      // k sub-tile, 32-row block of W
+    const int tid = threadIdx.x;
+    for (int i = tid; i < 32 * 32; i += 256) {
+        const int kk = i >> 5, nn = i & 31;
+        patch[kk][nn] = in[(size_t)(kt * 32 + kk) * N + b * 32 + nn];
     }
     __syncthreads();
-    for (int i = ty; i < 64; i += 4) {
-        const int c = c0 + i, r = r0 + tx;
-        if (c < cols && r < rows) out[(size_t)c * rows + r] = tile[tx][i];
+    if (tid < 128) {
+        // 2 groups x 64 pieces; piece id inside the group = r*4 + slot
+        const int grp = tid >> 6, pid = tid & 63;
+        const int r = pid >> 2, slot = pid & 3;
+        const int c = slot ^ ((r >> 2) & 3);
+        const int rho = grp * 16 + r;
+        const int nloc = ((rho >> 2) & 1) * 16 + (rho >> 3) * 4 + (rho & 3);
+        uint16_t v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = patch[c * 8 + i][nloc];
+        const size_t block = ((size_t)(b * 2 + grp) * (size_t)(K >> 5) + kt) * 512;  // in uint16 units
+        uint4 q;
+        q.x = v[0] | ((uint32_t)v[1] << 16);
+        q.y = v[2] | ((uint32_t)v[3] << 16);
+        q.z = v[4] | ((uint32_t)v[5] << 16);
+        q.w = v[6] | ((uint32_t)v[7] << 16);
+        *reinterpret_cast<uint4*>(out + block + pid * 8) = q;
     }
 }
 
@@ -92,9 +113,9 @@ hipError_t launch_combine(const moe_shape& s, const void* y_perm, const int32_t*
     return hipGetLastError();
 }
 
-hipError_t launch_transpose(const void* in, int rows, int cols, void* out, hipStream_t st) {
-    const dim3 grid((cols + 63) / 64, (rows + 63) / 64);
-    hipLaunchKernelGGL(transpose_kernel, grid, dim3(256), 0, st, (const uint16_t*)in, rows, cols, (uint16_t*)out);
+hipError_t launch_pack_weight(const void* in, int rows, int cols, void* out, hipStream_t st) {
+    const dim3 grid(rows / 32, cols / 32);   // rows = K, cols = N
+    hipLaunchKernelGGL(pack_weight_kernel, grid, dim3(256), 0, st, (const uint16_t*)in, rows, cols, (uint16_t*)out);
     return hipGetLastError();
 }
 

@@ -16,7 +16,7 @@ __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_
 
 // One m-tile of the grouped GEMMs: rows [row0, row0+nrows) of one group.
 //   routed group : group = expert id, row0 = permuted row, srow = -1
-//   shared group : group = E + s,     row0 = first token,  srow = s * T (row offset inside the shared region)
+//   shared group : group = E + s,     row0 = first token,  srow = s * t_pad (row offset inside the shared region of h)
 struct TileDesc {
     int32_t group;
     int32_t row0;
@@ -49,7 +49,8 @@ struct GemmArgs {
     int32_t xcd_remap;
     int32_t small_tiles;       // 1: a short tail tile runs the 128/64/32-row variant
     int32_t out_fp32;          // GEMM2: 1 = y stored as fp32, 0 = bf16 (GEMM1 always stores bf16)
-    int32_t k_step_bytes;      // bytes the K pointers advance per tile: BK*2; 0 only for the cache-resident timing probe
+    int32_t k_step_on;         // 1: K offsets advance per sub-tile; 0 only for the cache-resident timing probe
+    int32_t t_pad;             // T rounded up to 16: rows of one shared expert's block of h
 };
 
 struct GemmConfig {
@@ -87,6 +88,12 @@ hipError_t ffn_gemm_init();  // one-time function attributes (dynamic LDS size)
 
 hipError_t launch_combine(const moe_shape& s, const void* y_perm, const int32_t* inv_perm, const float* w,
                           const void* y_shared, void* out, bool y_fp32, bool out_fp32, hipStream_t st);
-hipError_t launch_transpose(const void* in, int rows, int cols, void* out, hipStream_t st);
+hipError_t launch_pack_weight(const void* in, int rows, int cols, void* out, hipStream_t st);
+
+// Rows of the h scratch: routed rows and each shared expert's rows start on a 16-row block boundary.
+inline int64_t h_rows(const moe_shape& s) {
+    const int64_t R = (int64_t)s.T * s.top_k;
+    return ((R + 15) & ~(int64_t)15) + (int64_t)s.num_shared * ((s.T + 15) & ~15);
+}
 
 }  // namespace moe

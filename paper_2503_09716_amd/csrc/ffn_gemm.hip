@@ -4,7 +4,15 @@
 //
 //   GEMM 1 (gated):  h[r, f]  = silu(X_e[r,:] . W1p_e[f,:]) * (X_e[r,:] . W3p_e[f,:])      -> bf16
 //   GEMM 2        :  y[r, n]  = h[r,:] . W2p_e[n,:]                                        -> fp32 / bf16
-// Both operands are K-contiguous ("packed" weights), so one tile routine serves both.
+// One tile routine serves both.  Weights and h are stored TILED: a matrix [N, K] is cut into
+// blocks of 16 rows x 32 k (1 KiB) laid out block-row-major ([N/16][K/32] blocks), and the 64
+// 16-byte pieces inside a block are in exactly the order the tile routine wants them in LDS
+// (row-major rows of 64 bytes, piece slot = piece ^ ((row/4)&3)).  One direct-to-LDS load of a
+// wavefront then reads 1 KiB of consecutive memory (8 full 128-byte lines) instead of 16
+// half-lines from 16 distant rows, which halves the number of L1->L2 requests in flight; the
+// L1's pending-request capacity, not bandwidth, is what the row-major form ran into
+// (TCP_PENDING_STALL_CYCLES at half of all cycles).  Weight rows are additionally permuted
+// inside each 32-row block by the pack step (see below); x is read row-major through the gather.
 //
 // Tile routine (one workgroup = NW wavefronts in a WM x WN grid):
 //   * macro tile: BM rows of X (256/128/64/32) x 256 rows of W (GEMM 1: 128 gate + 128 up rows,
@@ -109,9 +117,12 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
     const int n0 = n_tile * BN;
     const bool shared = d.srow >= 0;
     const int nseg = (!GATED && shared) ? p.nseg_shared : 1;
-    const int kstep = p.k_step_bytes;
+    const int KT = K / BK;   // sub-tiles per segment (>= 2)
+    // K step in bytes: one 1 KiB block for tiled operands, 64 bytes along a row for row-major x
+    const int kstep_w = p.k_step_on ? 1024 : 0;
+    const int kstep_x = p.k_step_on ? (GATED ? ROWB : 1024) : 0;
     const char* const a_base = shared ? p.a_shared : p.a_routed;
-    const size_t a_seg_stride = (size_t)p.T * (size_t)K * 2;
+    const size_t a_seg_stride = (size_t)p.t_pad * (size_t)K * 2;   // one shared expert's block of h
 
     // ------------------------------------------------------------------ loader setup
     // Wave-load q fills LDS bytes [q*1024, q*1024+1024) of a stage: 16 rows x 4 pieces.
@@ -131,27 +142,34 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
             int r = q * 16 + lrow;
             if (r > d.nrows - 1) r = d.nrows - 1;     // padded rows re-read the last valid row
             int grow = d.row0 + r;
-            if (GATED && !shared && p.row_token) grow = p.row_token[grow];
-            loff[i] = (uint32_t)grow * (uint32_t)(K * 2) + (uint32_t)(lpiece * 16);
+            if (GATED) {
+                // x: row-major [rows, K]
+                if (!shared && p.row_token) grow = p.row_token[grow];
+                loff[i] = (uint32_t)grow * (uint32_t)(K * 2) + (uint32_t)(lpiece * 16);
+            } else {
+                // h: tiled; the piece this lane needs sits at slot piece ^ ((row%16)/4) of its row
+                const int rr = grow & 15;
+                loff[i] = (uint32_t)(grow >> 4) * (uint32_t)(KT * 1024) + (uint32_t)(rr * 64 + ((lpiece ^ (rr >> 2)) << 4));
+            }
         } else {
-            const int wr = (q - NQX) * 16 + lrow;     // LDS row inside the W region, 0..255
-            const int blk = wr >> 5, rho = wr & 31;   // 32-row block, MFMA row inside it
-            const int nloc = ((rho >> 2) & 1) * 16 + (rho >> 3) * 4 + (rho & 3);
-            int n = n0 + (GATED ? (blk & 3) : blk) * 32 + nloc;
-            if (n > N - 1) n = N - 1;
-            loff[i] = (uint32_t)n * (uint32_t)(K * 2) + (uint32_t)(lpiece * 16);
+            // W: tiled and row-permuted by the pack step, so LDS rows (q-NQX)*16 .. +15 of the W region
+            // are one 1 KiB block: group index n0/16 + (q-NQX), in lane order.
+            const int qw = q - NQX;
+            int grp = (n0 >> 4) + (GATED ? (qw & 7) : qw);
+            if (grp > (N >> 4) - 1) grp = (N >> 4) - 1;
+            loff[i] = (uint32_t)grp * (uint32_t)(KT * 1024) + (uint32_t)(lane * 16);
         }
     }
     lds_t const ring = (lds_t)lds;
     __amdgpu_buffer_rsrc_t rs_x, rs_w, rs_u;   // X, W (gate / down), W (up)
-    int koff = 0;                              // byte offset along K of the sub-tile being loaded
+    int koff_x = 0, koff_w = 0;                // byte offsets along K of the sub-tile being loaded
 
     // Enqueues direct-to-LDS load i of the sub-tile at `koff` into ring stage `stage`.
     auto issue_one = [&](const int i, const int stage) __attribute__((always_inline)) {
         lptr_t dst = (lptr_t)(ring + stage * RING_STRIDE + (i * NW + wave) * 1024);
-        if (i < NLX) buffer_load16_to_lds(rs_x, dst, loff[i], koff);
-        else if (GATED && (i - NLX) * NW >= 8) buffer_load16_to_lds(rs_u, dst, loff[i], koff);
-        else buffer_load16_to_lds(rs_w, dst, loff[i], koff);
+        if (i < NLX) buffer_load16_to_lds(rs_x, dst, loff[i], koff_x);
+        else if (GATED && (i - NLX) * NW >= 8) buffer_load16_to_lds(rs_u, dst, loff[i], koff_w);
+        else buffer_load16_to_lds(rs_w, dst, loff[i], koff_w);
     };
 
     // ------------------------------------------------------------------ reader setup
@@ -228,7 +246,6 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
     using T_ = std::true_type;
     using F_ = std::false_type;
 
-    const int KT = K / BK;   // sub-tiles per segment (>= 2)
     using I0 = std::integral_constant<int, 0>;
     // GEMM 2 on shared experts walks `nseg` K-concatenated segments (one per shared expert);
     // every other tile has one segment.  The pipeline drains and restarts between segments.
@@ -237,14 +254,16 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
         rs_x = uniform_rsrc(a_base + (size_t)seg * a_seg_stride);
         rs_w = uniform_rsrc(p.w_a[d.group + seg]);
         if (GATED) rs_u = uniform_rsrc(p.w_b[d.group]);
-        koff = 0;
+        koff_x = 0;
+        koff_w = 0;
         // prologue: sub-tiles 0 .. NS-2 go out, wait for sub-tile 0
 #pragma unroll
         for (int s = 0; s < NS - 1; ++s) {
             if (s < KT) {
 #pragma unroll
                 for (int i = 0; i < NL; ++i) issue_one(i, s);
-                koff += kstep;
+                koff_x += kstep_x;
+                koff_w += kstep_w;
             }
         }
         if (KT >= NS - 1) ring_sync<(NS - 2) * NL>();
@@ -262,7 +281,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
             // issued above and have returned (lgkmcnt(0)) before any wave passes.
             ring_sync<(NS - 3) * NL + NL0>();
             half(T_{}, T_{}, std::integral_constant<int, NL0>{}, std::integral_constant<int, NL>{}, 1, nxt, 0, ld);
-            koff += kstep;
+            koff_x += kstep_x;
+            koff_w += kstep_w;
         }
         // tail: nothing left to load; conservative waits
         for (; t < KT - 1; ++t) {
@@ -287,10 +307,15 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
         if (r >= d.nrows) continue;
         char* orow = out + (size_t)(orow_base + r) * (size_t)N * 2;
         if (GATED) {
+            // h is written tiled: block (row/16, col/32), row (row%16), piece slot = piece ^ ((row%16)/4)
+            const int ro = orow_base + r, rr = ro & 15, sw = rr >> 2;
+            char* hrow = out + ((size_t)(ro >> 4) * (size_t)(N >> 5)) * 1024 + rr * 64;
 #pragma unroll
             for (int j = 0; j < TJH; ++j) {
                 const int col = n0 + (bw0 + j) * 32 + g * 16;
                 if (col >= N) continue;
+                char* hblk = hrow + (size_t)(col >> 5) * 1024;
+                const int c0 = (col & 31) >> 3;
                 bf16x8 o0, o1;
 #pragma unroll
                 for (int q = 0; q < 8; ++q) {
@@ -300,8 +325,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
                     o0[q] = (__bf16)(g0 * __builtin_amdgcn_rcpf(1.0f + __expf(-g0)) * u0);
                     o1[q] = (__bf16)(g1 * __builtin_amdgcn_rcpf(1.0f + __expf(-g1)) * u1);
                 }
-                *reinterpret_cast<bf16x8*>(orow + (size_t)col * 2) = o0;
-                *reinterpret_cast<bf16x8*>(orow + (size_t)col * 2 + 16) = o1;
+                *reinterpret_cast<bf16x8*>(hblk + ((c0 ^ sw) << 4)) = o0;
+                *reinterpret_cast<bf16x8*>(hblk + (((c0 + 1) ^ sw) << 4)) = o1;
                 __builtin_amdgcn_sched_barrier(0);   // one block at a time: keeps accumulator reads from piling up
             }
         } else if (p.out_fp32) {
@@ -408,7 +433,7 @@ __global__ __launch_bounds__(512, 2) void ffn_gemm_kernel8(const GemmArgs p) {
 // from expert_offsets.  Order: shared expert 0, routed experts, shared experts 1.. (the down
 // GEMM takes the first two parts only: shared experts are concatenated along K there).
 // A group of n rows becomes ceil(n/tm) tiles; the kernel runs a short variant on a short tail.
-__global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict__ offsets, int T, int E, int Ns,
+__global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict__ offsets, int T, int t_pad, int E, int Ns,
                                                        int tm_up, int tm_down, PlanHeader* __restrict__ plan,
                                                        TileDesc* __restrict__ descs_up, TileDesc* __restrict__ descs_down) {
     __shared__ int first[256];
@@ -422,7 +447,7 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
         else {
             if (Ns > 0) pos -= 1;
             if (pos < E) { group = pos; row_begin = offsets[pos]; rows = offsets[pos + 1] - row_begin; srow = -1; }
-            else { const int s = pos - E + 1; group = E + s; rows = T; row_begin = 0; srow = s * T; }
+            else { const int s = pos - E + 1; group = E + s; rows = T; row_begin = 0; srow = s * t_pad; }
         }
     }
     for (int which = 0; which < 2; ++which) {
@@ -480,7 +505,7 @@ hipError_t ffn_gemm_init() {
 
 hipError_t launch_ffn_plan(const moe_shape& s, const int32_t* offsets, int tm_up, int tm_down, PlanHeader* plan,
                            TileDesc* descs_up, TileDesc* descs_down, hipStream_t st) {
-    hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(256), 0, st, offsets, s.T, s.E, s.num_shared, tm_up, tm_down,
+    hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(256), 0, st, offsets, s.T, (s.T + 15) & ~15, s.E, s.num_shared, tm_up, tm_down,
                        plan, descs_up, descs_down);
     return hipGetLastError();
 }

@@ -81,7 +81,7 @@ def test_fused_equals_staged_bit_for_bit(moe):
     perm = torch.empty(R, dtype=torch.int32, device=dev); inv = torch.empty_like(perm)
     ws = moe.new_workspace(sh)
     moe.permute(sh, gl.x, idx, x_perm, off, perm, inv, None, ws)
-    h = torch.empty((R + cfg.T * cfg.num_shared, cfg.F), dtype=torch.bfloat16, device=dev)
+    h = moe.new_h_scratch(sh)
     y = torch.empty((R, cfg.H), dtype=torch.float32, device=dev)
     ysh = torch.empty((cfg.T, cfg.H), dtype=torch.float32, device=dev)
     moe.grouped_ffn(sh, x_perm, None, gl.x, off, gl.w1p, gl.w3p, gl.w2p, h, y, ysh, ws)

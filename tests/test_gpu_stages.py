@@ -146,7 +146,7 @@ def run_ffn_stage(moe, cfg, idx_h, wave_rows=2, small_tiles=1, use_row_token=Fal
     rtok = torch.empty(R, dtype=torch.int32, device="cuda")
     ws = moe.new_workspace(shape)
     moe.permute(shape, li.x, idx, x_perm, off, perm, inv, rtok, ws)
-    h = torch.empty((R + cfg.T * cfg.num_shared, cfg.F), dtype=torch.bfloat16, device="cuda")
+    h = moe.new_h_scratch(shape)
     ydt = torch.float32 if y_fp32 else torch.bfloat16
     y = torch.full((R, cfg.H), float("nan"), dtype=ydt, device="cuda")
     ysh = torch.full((cfg.T, cfg.H), float("nan"), dtype=ydt, device="cuda") if cfg.num_shared else None
@@ -247,7 +247,7 @@ def test_grouped_ffn_exact_scaling(moe):
     perm = torch.empty(R, dtype=torch.int32, device="cuda"); inv = torch.empty_like(perm)
     ws = moe.new_workspace(shape)
     moe.permute(shape, li.x, idx, x_perm, off, perm, inv, None, ws)
-    h = torch.empty((R, cfg.F), dtype=torch.bfloat16, device="cuda")
+    h = moe.new_h_scratch(shape)
     y2 = torch.empty((R, cfg.H), dtype=torch.float32, device="cuda")
     moe.grouped_ffn(shape, x_perm, None, None, off, w1p, w3p, w2p, h, y2, None, ws)
     torch.cuda.synchronize()
@@ -300,11 +300,27 @@ def test_combine(moe, T, H, k, shared, y_fp32):
         moe.set_option("out_fp32", 0)
 
 
-def test_pack_weight_is_a_transpose(moe):
-    w = normal_bf16(4, 0, (192, 1000), 0.02, "cuda")
+def packed_reference(w: np.ndarray) -> np.ndarray:
+    """The packed layout as include/moe.h words it, written out element by element."""
+    K, N = w.shape
+    out = np.empty(K * N, w.dtype)
+    for n in range(N):
+        b, rho = divmod(n, 32)          # which logical row does packed row n hold?
+        src = 32 * b + ((rho // 4) & 1) * 16 + (rho // 8) * 4 + (rho & 3)
+        g, r = divmod(n, 16)
+        for kt in range(K // 32):
+            base = (g * (K // 32) + kt) * 512
+            for c in range(4):
+                slot = c ^ ((r // 4) & 3)
+                out[base + r * 32 + slot * 8: base + r * 32 + slot * 8 + 8] = w[kt * 32 + c * 8: kt * 32 + c * 8 + 8, src]
+    return out
+
+
+def test_pack_weight_layout(moe):
+    w = normal_bf16(4, 0, (96, 160), 0.02, "cuda")
     p = moe.pack_weight(w)
     torch.cuda.synchronize()
-    assert torch.equal(p, w.t().contiguous())
+    np.testing.assert_array_equal(torch_bf16_to_u16(p), packed_reference(torch_bf16_to_u16(w)))
 
 
 def test_error_paths(moe):
