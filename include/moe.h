@@ -103,6 +103,9 @@ size_t moe_h_scratch_bytes(const moe_shape* shape);
  *   "small_tiles"     0 | 1   use 128/64/32-row tiles for the ragged tail of an expert
  *   "gemm_tile_rows_up" / "gemm_tile_rows_down"  0 | 128 | 256   rows per m-tile of the gate/up and
  *                             the down GEMM; 0 (default) picks per launch from the tile count
+ *   "x_tiled"         -1|0|1  moe_layer: 1 gathers x once into a block-tiled x_perm that the gate/up GEMM
+ *                             loads in 1 KiB pieces, 0 fuses the gather into that GEMM's loads, -1 (default)
+ *                             chooses by expert width.  Same results bit for bit.
  *   "probe_k_resident" 0 | 1  timing probe only: the GEMMs re-read their first K tile at every K step
  *                             (operands stay cache resident, RESULTS ARE MEANINGLESS); default 0
  *   "y_fp32"          0 | 1   dtype of y_perm / y_shared: 1 (default) fp32, 0 bf16.  bf16 halves the
@@ -174,8 +177,9 @@ moe_status moe_grouped_ffn(moe_ctx* ctx, const moe_shape* shape, const void* x_p
 moe_status moe_combine(moe_ctx* ctx, const moe_shape* shape, const void* y_perm, const int32_t* inv_perm,
                        const float* topk_w, const void* y_shared_or_null, void* out, void* hip_stream);
 
-/* The whole expert module on one stream: route -> permute (indices only; the row gather is
- * fused into the first GEMM's loads) -> grouped FFN -> combine.  Same results as the staged
+/* The whole expert module on one stream: route -> permute (indices; the row gather is fused
+ * into the first GEMM's loads, or done once into a tiled x_perm: option "x_tiled") -> grouped
+ * FFN -> combine.  Same results as the staged
  * calls bit for bit.  All intermediates live in `workspace`.  out [T,H] is bf16, or fp32
  * under option "out_fp32" = 1. */
 moe_status moe_layer(moe_ctx* ctx, const moe_shape* shape, const void* x_bf16, const void* wg_bf16,

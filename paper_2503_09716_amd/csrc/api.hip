@@ -26,7 +26,7 @@ struct ProfRec {
 struct moe_ctx {
     int device = 0;
     char err[512] = {0};
-    GemmConfig gemm{2, 4, 8, 1, 1, 0, 0, 0};
+    GemmConfig gemm{2, 4, 8, 1, 1, 0, 0, -1, 0};
     bool y_fp32 = true;    // dtype of y_perm / y_shared
     bool out_fp32 = false; // dtype of the layer output
     // Ring of device pointer tables [3][MAX_GROUPS] (W1p, W3p, W2p), each with a pinned host
@@ -86,7 +86,7 @@ inline size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
 // Workspace layout: fixed order, every region 256-byte aligned.
 struct Layout {
-    size_t topk_idx, topk_w, offsets, perm, inv_perm, row_token, chunk_counts, plan, descs_up, descs_down, h, y_perm, y_shared, total;
+    size_t topk_idx, topk_w, offsets, perm, inv_perm, row_token, chunk_counts, plan, descs_up, descs_down, x_tiled, h, y_perm, y_shared, total;
 };
 
 Layout make_layout(const moe_shape& s) {
@@ -104,6 +104,7 @@ Layout make_layout(const moe_shape& s) {
     L.plan = take(sizeof(PlanHeader));
     L.descs_up = take((size_t)max_mtiles(s, 128) * sizeof(TileDesc));
     L.descs_down = take((size_t)max_mtiles(s, 128) * sizeof(TileDesc));
+    L.x_tiled = take(((R + 15) & ~(size_t)15) * s.H * 2);
     L.h = take((size_t)h_rows(s) * s.F * 2);
     L.y_perm = take(R * s.H * 4);  // sized for fp32 y
     L.y_shared = take(Rs ? (size_t)s.T * s.H * 4 : 0);
@@ -200,9 +201,11 @@ int pick_tile_rows(const moe_shape& s, int n_tiles, int nseg) {
     return best_tm;
 }
 
+// x_perm_tiled: when non-null, the routed rows of GEMM 1 are read from it (tiled layout) and
+// x_perm / row_token are not used for them.
 moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int32_t* row_token, const void* x,
-                   const int32_t* offsets, void** tab, char* ws, void* h, void* y_perm, void* y_shared,
-                   hipStream_t st) {
+                   const void* x_perm_tiled, const int32_t* offsets, void** tab, char* ws, void* h, void* y_perm,
+                   void* y_shared, hipStream_t st) {
     const Layout L = make_layout(s);
     PlanHeader* plan = (PlanHeader*)(ws + L.plan);
     TileDesc* descs_up = (TileDesc*)(ws + L.descs_up);
@@ -228,9 +231,10 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     // GEMM 1: [rows, H] x W1p/W3p [F, H] -> h [rows, F]
     a.descs = descs_up;
     a.max_mtiles = (int)max_mtiles(s, tm_up);
-    a.a_routed = (const char*)(row_token ? x : x_perm);
+    a.a_routed = (const char*)(x_perm_tiled ? x_perm_tiled : (row_token ? x : x_perm));
     a.a_shared = (const char*)x;
-    a.row_token = row_token;
+    a.row_token = x_perm_tiled ? nullptr : row_token;
+    a.a_tiled = x_perm_tiled ? 1 : 0;
     a.w_a = (const void* const*)tab;
     a.w_b = (const void* const*)(tab + MAX_GROUPS);
     a.out_routed = (char*)h;
@@ -249,6 +253,7 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     a.a_routed = (const char*)h;
     a.a_shared = (const char*)h + Rpad * s.F * 2;
     a.row_token = nullptr;
+    a.a_tiled = 0;
     a.w_a = (const void* const*)(tab + 2 * MAX_GROUPS);
     a.w_b = nullptr;
     a.out_routed = (char*)y_perm;
@@ -325,6 +330,7 @@ moe_status moe_set_option(moe_ctx* c, const char* key, int32_t v) {
     if (!strcmp(key, "small_tiles") && (v == 0 || v == 1)) { c->gemm.small_tiles = v; return MOE_OK; }
     if (!strcmp(key, "gemm_tile_rows_up") && (v == 0 || v == 128 || v == 256)) { c->gemm.tile_rows_up = v; return MOE_OK; }
     if (!strcmp(key, "gemm_tile_rows_down") && (v == 0 || v == 128 || v == 256)) { c->gemm.tile_rows_down = v; return MOE_OK; }
+    if (!strcmp(key, "x_tiled") && v >= -1 && v <= 1) { c->gemm.x_tiled = v; return MOE_OK; }
     if (!strcmp(key, "probe_k_resident") && (v == 0 || v == 1)) { c->gemm.probe_k_resident = v; return MOE_OK; }
     if (!strcmp(key, "y_fp32") && (v == 0 || v == 1)) { c->y_fp32 = v != 0; return MOE_OK; }
     if (!strcmp(key, "out_fp32") && (v == 0 || v == 1)) { c->out_fp32 = v != 0; return MOE_OK; }
@@ -386,7 +392,7 @@ moe_status moe_grouped_ffn(moe_ctx* c, const moe_shape* s, const void* x_perm, c
     hipStream_t hs = (hipStream_t)stream;
     void** tab = nullptr;
     if (moe_status st = weight_table(c, s->E + s->num_shared, w1p, w3p, w2p, hs, &tab)) return st;
-    return run_ffn(c, *s, x_perm, row_token, x, offsets, tab, (char*)ws, h, y_perm, y_shared, hs);
+    return run_ffn(c, *s, x_perm, row_token, x, nullptr, offsets, tab, (char*)ws, h, y_perm, y_shared, hs);
 }
 
 moe_status moe_combine(moe_ctx* c, const moe_shape* s, const void* y_perm, const int32_t* inv_perm, const float* w,
@@ -425,7 +431,18 @@ moe_status moe_layer(moe_ctx* c, const moe_shape* s, const void* x, const void* 
         StageTimer tm(c, hs, MOE_STAGE_PERMUTE_INDEX);
         HIP_TRY(c, launch_permute_index(*s, idx, (int32_t*)(w8 + L.chunk_counts), offsets, perm, inv_perm, row_token, hs));
     }
-    if (moe_status st = run_ffn(c, *s, nullptr, row_token, x, offsets, tab, w8, w8 + L.h, w8 + L.y_perm, y_shared, hs))
+    // The gather is either fused into GEMM 1's loads (row-major x, 64-byte pieces from 16 distant
+    // rows per load) or done once into a tiled x_perm (one extra pass over T*k*H*2 bytes, after
+    // which GEMM 1 loads whole 1 KiB blocks).  The extra pass pays off when each x row is re-read
+    // by many n-tiles, i.e. for wide experts.
+    const bool tiled = c->gemm.x_tiled == 1 || (c->gemm.x_tiled < 0 && s->F >= 4096);
+    const void* xt = nullptr;
+    if (tiled) {
+        StageTimer tm(c, hs, MOE_STAGE_PERMUTE_GATHER);
+        HIP_TRY(c, launch_permute_gather_tiled(*s, x, row_token, w8 + L.x_tiled, hs));
+        xt = w8 + L.x_tiled;
+    }
+    if (moe_status st = run_ffn(c, *s, nullptr, row_token, x, xt, offsets, tab, w8, w8 + L.h, w8 + L.y_perm, y_shared, hs))
         return st;
     {
         StageTimer tm(c, hs, MOE_STAGE_COMBINE);

@@ -50,6 +50,7 @@ struct GemmArgs {
     int32_t small_tiles;       // 1: a short tail tile runs the 128/64/32-row variant
     int32_t out_fp32;          // GEMM2: 1 = y stored as fp32, 0 = bf16 (GEMM1 always stores bf16)
     int32_t k_step_on;         // 1: K offsets advance per sub-tile; 0 only for the cache-resident timing probe
+    int32_t a_tiled;           // GEMM1: routed rows of A come from a tiled x_perm (16 x 32 blocks) instead of row-major x
     int32_t t_pad;             // T rounded up to 16: rows of one shared expert's block of h
 };
 
@@ -61,6 +62,7 @@ struct GemmConfig {
     int small_tiles;
     int tile_rows_up;      // rows per m-tile of the gate/up GEMM: 0 = choose per launch, else 128 or 256
     int tile_rows_down;    // same for the down GEMM
+    int x_tiled;           // moe_layer: 1 = gather x into a tiled x_perm first, 0 = gather inside GEMM 1, -1 = choose
     int probe_k_resident;  // timing probe: every K step re-reads the first tile (results are meaningless)
 };
 
@@ -80,6 +82,9 @@ hipError_t launch_permute_index(const moe_shape& s, const int32_t* idx, int32_t*
                                 int32_t* perm, int32_t* inv_perm, int32_t* row_token, hipStream_t st);
 hipError_t launch_permute_gather(const moe_shape& s, const void* x, const int32_t* perm, void* x_perm,
                                  hipStream_t st);
+// x_perm in 16-row x 32-column blocks (the layout of h), rows past T*k in the last block undefined
+hipError_t launch_permute_gather_tiled(const moe_shape& s, const void* x, const int32_t* row_token, void* x_tiled,
+                                       hipStream_t st);
 
 hipError_t launch_ffn_plan(const moe_shape& s, const int32_t* offsets, int tm_up, int tm_down, PlanHeader* plan,
                            TileDesc* descs_up, TileDesc* descs_down, hipStream_t st);

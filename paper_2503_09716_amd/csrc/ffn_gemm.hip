@@ -120,7 +120,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
     const int KT = K / BK;   // sub-tiles per segment (>= 2)
     // K step in bytes: one 1 KiB block for tiled operands, 64 bytes along a row for row-major x
     const int kstep_w = p.k_step_on ? 1024 : 0;
-    const int kstep_x = p.k_step_on ? (GATED ? ROWB : 1024) : 0;
+    // A operand: h (GEMM 2) is always tiled; GEMM 1 reads x row-major (through the gather or for
+    // shared experts) unless the caller passed a tiled x_perm for the routed rows
+    const bool a_tiled = !GATED || (p.a_tiled && d.srow < 0);
+    const int kstep_x = p.k_step_on ? (a_tiled ? 1024 : ROWB) : 0;
     const char* const a_base = shared ? p.a_shared : p.a_routed;
     const size_t a_seg_stride = (size_t)p.t_pad * (size_t)K * 2;   // one shared expert's block of h
 
@@ -142,7 +145,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
             int r = q * 16 + lrow;
             if (r > d.nrows - 1) r = d.nrows - 1;     // padded rows re-read the last valid row
             int grow = d.row0 + r;
-            if (GATED) {
+            if (!a_tiled) {
                 // x: row-major [rows, K]
                 if (!shared && p.row_token) grow = p.row_token[grow];
                 loff[i] = (uint32_t)grow * (uint32_t)(K * 2) + (uint32_t)(lpiece * 16);

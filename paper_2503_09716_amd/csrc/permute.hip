@@ -150,7 +150,38 @@ __global__ __launch_bounds__(256) void permute_gather_kernel(const uint4* __rest
     }
 }
 
+// Gather into the tiled layout: one wavefront fills one 1 KiB block (16 permuted rows x 32
+// columns): lane l reads the 16-byte piece ((l%4) ^ ((l/16)%4)) of row 16g + l/4 and writes
+// slot l of the block, so every store instruction covers 1 KiB of consecutive memory.
+__global__ __launch_bounds__(256) void permute_gather_tiled_kernel(const char* __restrict__ x,
+                                                                   const int32_t* __restrict__ row_token, int R, int H,
+                                                                   char* __restrict__ xt) {
+    const int lane = threadIdx.x & 63;
+    const int KT = H >> 5;
+    const int nblocks = ((R + 15) >> 4) * KT;
+    const int nwaves = gridDim.x * 4;
+    const int piece = (lane & 3) ^ ((lane >> 4) & 3);
+    for (int b = blockIdx.x * 4 + (threadIdx.x >> 6); b < nblocks; b += nwaves) {
+        const int g = b / KT, kt = b - g * KT;
+        int r = g * 16 + (lane >> 2);
+        if (r > R - 1) r = R - 1;
+        const int t = row_token[r];
+        const uint4 v = *reinterpret_cast<const uint4*>(x + ((size_t)t * H + kt * 32 + piece * 8) * 2);
+        *reinterpret_cast<uint4*>(xt + (size_t)b * 1024 + lane * 16) = v;
+    }
+}
+
 }  // namespace
+
+hipError_t launch_permute_gather_tiled(const moe_shape& s, const void* x, const int32_t* row_token, void* x_tiled,
+                                       hipStream_t st) {
+    const int R = s.T * s.top_k;
+    const int nblocks = ((R + 15) / 16) * (s.H / 32);
+    const int blocks = (nblocks + 3) / 4 < 16384 ? (nblocks + 3) / 4 : 16384;
+    hipLaunchKernelGGL(permute_gather_tiled_kernel, dim3(blocks), dim3(256), 0, st, (const char*)x, row_token, R, s.H,
+                       (char*)x_tiled);
+    return hipGetLastError();
+}
 
 hipError_t launch_permute_index(const moe_shape& s, const int32_t* idx, int32_t* chunk_counts, int32_t* offsets,
                                 int32_t* perm, int32_t* inv_perm, int32_t* row_token, hipStream_t st) {

@@ -94,6 +94,21 @@ def test_fused_equals_staged_bit_for_bit(moe):
     assert torch.equal(v["expert_offsets"], off) and torch.equal(v["inv_perm"], inv)
 
 
+def test_tiled_gather_equals_fused_gather(moe):
+    """Option x_tiled: gathering x into a tiled x_perm first gives the same bits as the fused gather."""
+    for name, over in [("C4", dict(T=333, H=256, F=192)), ("C2", dict(T=520, H=192, F=256))]:
+        cfg = scaled_config(name, **over)
+        gl = P.GpuLayer(moe, make_layer_inputs(cfg, device="cuda"), host_weights=False)
+        outs = []
+        for v in (0, 1):
+            moe.set_option("x_tiled", v)
+            try:
+                outs.append(gl.run_layer(True))
+            finally:
+                moe.set_option("x_tiled", -1)
+        assert torch.equal(outs[0], outs[1])
+
+
 def test_layer_metamorphic_exact(moe):
     """Doubling W2 doubles the output bit-exactly; zero input gives zero output."""
     cfg = scaled_config("C1", T=200, H=128, F=128)
