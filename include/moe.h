@@ -128,10 +128,12 @@ moe_status moe_pack_weight(moe_ctx* ctx, const void* w_logical, int32_t rows, in
  * renormalize) * routed_scale.
  *   x_bf16 [T,H] device, wg_bf16 [H,E] device (logical layout), gate_bias [E] fp32 device or NULL
  *   topk_idx [T,k] int32 device out, topk_w [T,k] fp32 device out,
- *   logits_or_null [T,E] fp32 device out (for near-tie reports) or NULL. */
+ *   logits_or_null [T,E] fp32 device out (for near-tie reports) or NULL
+ *   workspace: device, at least moe_workspace_bytes(shape) (used when E > 16: the gate GEMM then
+ *   runs on the matrix cores and keeps its packed gate matrix and partial logits there). */
 moe_status moe_route(moe_ctx* ctx, const moe_shape* shape, const void* x_bf16, const void* wg_bf16,
                      const float* gate_bias, int32_t* topk_idx, float* topk_w, float* logits_or_null,
-                     void* hip_stream);
+                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Groups the T*k (token, rank) pairs by expert ("tokens routed to an expert", Table 1; the
  * counts are only known at run time, Sec. 4.3).  Order: ascending expert, then ascending

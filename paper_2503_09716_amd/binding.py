@@ -61,7 +61,7 @@ def load_library():
     lib.moe_h_scratch_bytes.restype = C.c_size_t
     lib.moe_set_option.argtypes = [C.c_void_p, C.c_char_p, C.c_int32]
     lib.moe_pack_weight.argtypes = [C.c_void_p, vp, C.c_int32, C.c_int32, vp, vp]
-    lib.moe_route.argtypes = [C.c_void_p, sp, vp, vp, f32p, i32p, f32p, f32p, vp]
+    lib.moe_route.argtypes = [C.c_void_p, sp, vp, vp, f32p, i32p, f32p, f32p, vp, C.c_size_t, vp]
     lib.moe_permute.argtypes = [C.c_void_p, sp, vp, i32p, vp, i32p, i32p, i32p, i32p, vp, C.c_size_t, vp]
     lib.moe_grouped_ffn.argtypes = [C.c_void_p, sp, vp, i32p, vp, i32p, tab, tab, tab, vp, vp, vp, vp, C.c_size_t, vp]
     lib.moe_combine.argtypes = [C.c_void_p, sp, vp, i32p, f32p, vp, vp, vp]
@@ -163,9 +163,9 @@ class Moe:
                 [self.pack_weight(w) for w in w2])
 
     # ---- staged calls ------------------------------------------------------------------
-    def route(self, shape, x, wg, bias, topk_idx, topk_w, logits=None):
+    def route(self, shape, x, wg, bias, topk_idx, topk_w, logits, workspace):
         self._check(self.lib.moe_route(self.h, C.byref(shape), _ptr(x), _ptr(wg), _ptr(bias), _ptr(topk_idx),
-                                       _ptr(topk_w), _ptr(logits), _stream()))
+                                       _ptr(topk_w), _ptr(logits), _ptr(workspace), workspace.numel(), _stream()))
 
     def permute(self, shape, x, topk_idx, x_perm, expert_offsets, perm, inv_perm, row_token, workspace):
         self._check(self.lib.moe_permute(self.h, C.byref(shape), _ptr(x), _ptr(topk_idx), _ptr(x_perm),

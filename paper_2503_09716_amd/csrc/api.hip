@@ -84,9 +84,25 @@ const char* shape_problem(const moe_shape* s, moe_status* st) {
 
 inline size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
+// Router through the GEMM tile routine (E > 16): experts padded to 32, K cut into `splits`
+// independent accumulation chains (shorter fp32 sums, and more tiles to fill the CUs), tiles
+// of `tm` tokens.  splits == 0: the streaming kernel is used instead.
+struct RouteGemm {
+    int splits, ep, tm;
+};
+RouteGemm route_gemm_config(const moe_shape& s) {
+    RouteGemm r{0, 0, 0};
+    if (s.E <= 16) return r;
+    r.ep = (s.E + 31) & ~31;
+    r.splits = (s.H % 256 == 0 && s.H >= 1024) ? 4 : (s.H % 128 == 0 ? 2 : 1);
+    r.tm = (int64_t)r.splits * ((s.T + 255) / 256) >= 512 ? 256 : 128;
+    return r;
+}
+
 // Workspace layout: fixed order, every region 256-byte aligned.
 struct Layout {
-    size_t topk_idx, topk_w, offsets, perm, inv_perm, row_token, chunk_counts, plan, descs_up, descs_down, x_tiled, h, y_perm, y_shared, total;
+    size_t topk_idx, topk_w, offsets, perm, inv_perm, row_token, chunk_counts, plan, descs_up, descs_down,
+        rt_plan, rt_table, rt_descs, rt_wg, rt_logits, x_tiled, h, y_perm, y_shared, total;
 };
 
 Layout make_layout(const moe_shape& s) {
@@ -104,6 +120,13 @@ Layout make_layout(const moe_shape& s) {
     L.plan = take(sizeof(PlanHeader));
     L.descs_up = take((size_t)max_mtiles(s, 128) * sizeof(TileDesc));
     L.descs_down = take((size_t)max_mtiles(s, 128) * sizeof(TileDesc));
+    // router GEMM (E > 16): plan, W pointer per K-split, tile list, packed gate matrix, partial logits
+    const RouteGemm rg = route_gemm_config(s);
+    L.rt_plan = take(rg.splits ? sizeof(PlanHeader) : 0);
+    L.rt_table = take(rg.splits ? 8 * sizeof(void*) : 0);
+    L.rt_descs = take(rg.splits ? (size_t)rg.splits * ((s.T + 127) / 128) * sizeof(TileDesc) : 0);
+    L.rt_wg = take(rg.splits ? (size_t)rg.ep * s.H * 2 : 0);
+    L.rt_logits = take(rg.splits ? (size_t)rg.splits * s.T * rg.ep * 4 : 0);
     L.x_tiled = take(((R + 15) & ~(size_t)15) * s.H * 2);
     L.h = take((size_t)h_rows(s) * s.F * 2);
     L.y_perm = take(R * s.H * 4);  // sized for fp32 y
@@ -185,6 +208,53 @@ moe_status weight_table(moe_ctx* c, int n, const void* const* w1, const void* co
     return MOE_OK;
 }
 
+moe_status run_route(moe_ctx* c, const moe_shape& s, const void* x, const void* wg, const float* bias, int32_t* idx,
+                     float* w, float* logits, char* ws, hipStream_t st) {
+    const RouteGemm rg = route_gemm_config(s);
+    if (!rg.splits) {
+        HIP_TRY(c, launch_route(s, x, wg, bias, idx, w, logits, st));
+        return MOE_OK;
+    }
+    const Layout L = make_layout(s);
+    PlanHeader* plan = (PlanHeader*)(ws + L.rt_plan);
+    const void** table = (const void**)(ws + L.rt_table);
+    TileDesc* descs = (TileDesc*)(ws + L.rt_descs);
+    const int k_split = s.H / rg.splits;
+    HIP_TRY(c, launch_pack_weight(wg, s.H, s.E, rg.ep, ws + L.rt_wg, st));
+    HIP_TRY(c, launch_route_plan(s.T, rg.tm, rg.splits, ws + L.rt_wg, k_split / 32, plan, descs, table, st));
+    GemmArgs a;
+    memset(&a, 0, sizeof(a));
+    a.a_routed = (const char*)x;
+    a.a_shared = (const char*)x;
+    a.w_a = (const void* const*)table;
+    a.out_routed = ws + L.rt_logits;
+    a.out_shared = ws + L.rt_logits;
+    a.descs = descs;
+    a.plan = plan;
+    a.K = k_split;
+    a.N = rg.ep;
+    a.T = s.T;
+    a.nseg_shared = 1;
+    a.n_tiles = (rg.ep + 255) / 256;
+    a.max_mtiles = rg.splits * ((s.T + rg.tm - 1) / rg.tm);
+    a.group_m = 8;
+    a.xcd_remap = 0;
+    a.small_tiles = 1;
+    a.out_fp32 = 1;
+    a.k_step_on = 1;
+    a.lda_bytes = s.H * 2;
+    a.kt_w = s.H / 32;
+    a.split_rows = s.T;
+    a.a_tiled = 0;
+    a.t_pad = (s.T + 15) & ~15;
+    GemmConfig cfg = c->gemm;
+    cfg.waves = 4;
+    cfg.wave_rows = 2;
+    HIP_TRY(c, launch_ffn_gemm(false, a, cfg, st));
+    HIP_TRY(c, launch_route_topk(s, (const float*)(ws + L.rt_logits), rg.splits, rg.ep, bias, idx, w, logits, st));
+    return MOE_OK;
+}
+
 // Rows per m-tile for one GEMM.  Tiles of 256 rows are the efficient shape (measured: the
 // 128-row shape runs at ~0.75 of their rate); 128 rows only win when a launch has so few
 // 256-row tiles that most CUs would idle in its last round.
@@ -228,6 +298,7 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     a.out_fp32 = 0;
     a.k_step_on = c->gemm.probe_k_resident ? 0 : 1;
     a.t_pad = (s.T + 15) & ~15;
+    a.split_rows = 0;
     // GEMM 1: [rows, H] x W1p/W3p [F, H] -> h [rows, F]
     a.descs = descs_up;
     a.max_mtiles = (int)max_mtiles(s, tm_up);
@@ -241,6 +312,8 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     a.out_shared = (char*)h + Rpad * s.F * 2;
     a.K = s.H;
     a.N = s.F;
+    a.lda_bytes = s.H * 2;
+    a.kt_w = s.H / 32;
     a.nseg_shared = 1;
     a.n_tiles = nt_up;
     {
@@ -253,13 +326,15 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     a.a_routed = (const char*)h;
     a.a_shared = (const char*)h + Rpad * s.F * 2;
     a.row_token = nullptr;
-    a.a_tiled = 0;
+    a.a_tiled = 3;
     a.w_a = (const void* const*)(tab + 2 * MAX_GROUPS);
     a.w_b = nullptr;
     a.out_routed = (char*)y_perm;
     a.out_shared = (char*)y_shared;
     a.K = s.F;
     a.N = s.H;
+    a.lda_bytes = s.F * 2;
+    a.kt_w = s.F / 32;
     a.nseg_shared = s.num_shared > 0 ? s.num_shared : 1;
     a.out_fp32 = c->y_fp32 ? 1 : 0;
     a.n_tiles = nt_down;
@@ -344,18 +419,18 @@ moe_status moe_pack_weight(moe_ctx* c, const void* w, int32_t rows, int32_t cols
     if (rows < 32 || cols < 32 || rows % 32 || cols % 32) return fail(c, MOE_E_ARG, "pack: rows, cols must be positive multiples of 32");
     if ((int64_t)rows * cols * 2 >= ((int64_t)1 << 32)) return fail(c, MOE_E_UNSUPPORTED, "pack: matrix reaches 4 GiB");
     HIP_TRY(c, hipSetDevice(c->device));
-    HIP_TRY(c, launch_pack_weight(w, rows, cols, packed, (hipStream_t)stream));
+    HIP_TRY(c, launch_pack_weight(w, rows, cols, cols, packed, (hipStream_t)stream));
     return MOE_OK;
 }
 
 moe_status moe_route(moe_ctx* c, const moe_shape* s, const void* x, const void* wg, const float* bias,
-                     int32_t* idx, float* w, float* logits, void* stream) {
+                     int32_t* idx, float* w, float* logits, void* ws, size_t ws_bytes, void* stream) {
     if (moe_status st = check_common(c, s)) return st;
     if (!x || !wg || !idx || !w) return fail(c, MOE_E_ARG, "route: NULL pointer");
+    if (moe_status st = check_ws(c, s, ws, ws_bytes)) return st;
     hipStream_t hs = (hipStream_t)stream;
     StageTimer tm(c, hs, MOE_STAGE_ROUTE);
-    HIP_TRY(c, launch_route(*s, x, wg, bias, idx, w, logits, hs));
-    return MOE_OK;
+    return run_route(c, *s, x, wg, bias, idx, w, logits, (char*)ws, hs);
 }
 
 moe_status moe_permute(moe_ctx* c, const moe_shape* s, const void* x, const int32_t* idx, void* x_perm,
@@ -425,7 +500,7 @@ moe_status moe_layer(moe_ctx* c, const moe_shape* s, const void* x, const void* 
     void* y_shared = s->num_shared > 0 ? (void*)(w8 + L.y_shared) : nullptr;
     {
         StageTimer tm(c, hs, MOE_STAGE_ROUTE);
-        HIP_TRY(c, launch_route(*s, x, wg, bias, idx, tw, nullptr, hs));
+        if (moe_status st = run_route(c, *s, x, wg, bias, idx, tw, nullptr, w8, hs)) return st;
     }
     {
         StageTimer tm(c, hs, MOE_STAGE_PERMUTE_INDEX);

@@ -68,6 +68,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const char* __restrict__ y
 // 32b + ((rho/4)&1)*16 + (rho/8)*4 + (rho&3), the order in which the MFMA accumulator
 // registers of a lane enumerate output columns.
 // One workgroup transposes a 32 k x 32 n patch through LDS.
+// N columns exist in `in`; blocks past them (the router pads its expert count to 32) are zero.
 __global__ __launch_bounds__(256) void pack_weight_kernel(const uint16_t* __restrict__ in, int K, int N,
                                                           uint16_t* __restrict__ out) {
     __shared__ uint16_t patch[32][34];
@@ -75,7 +76,8 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const uint16_t* __rest
     const int tid = threadIdx.x;
     for (int i = tid; i < 32 * 32; i += 256) {
         const int kk = i >> 5, nn = i & 31;
-        patch[kk][nn] = in[(size_t)(kt * 32 + kk) * N + b * 32 + nn];
+        const int n = b * 32 + nn;
+        patch[kk][nn] = n < N ? in[(size_t)(kt * 32 + kk) * N + n] : (uint16_t)0;
     }
     __syncthreads();
     if (tid < 128) {
@@ -113,8 +115,8 @@ hipError_t launch_combine(const moe_shape& s, const void* y_perm, const int32_t*
     return hipGetLastError();
 }
 
-hipError_t launch_pack_weight(const void* in, int rows, int cols, void* out, hipStream_t st) {
-    const dim3 grid(rows / 32, cols / 32);   // rows = K, cols = N
+hipError_t launch_pack_weight(const void* in, int rows, int cols, int cols_padded, void* out, hipStream_t st) {
+    const dim3 grid(rows / 32, cols_padded / 32);   // rows = K, cols = N
     hipLaunchKernelGGL(pack_weight_kernel, grid, dim3(256), 0, st, (const uint16_t*)in, rows, cols, (uint16_t*)out);
     return hipGetLastError();
 }

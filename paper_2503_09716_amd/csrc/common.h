@@ -16,6 +16,7 @@ __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_
 
 // One m-tile of the grouped GEMMs: rows [row0, row0+nrows) of one group.
 //   routed group : group = expert id, row0 = permuted row, srow = -1
+//   router GEMM  : group = K-split index s, row0 = first token, srow = -1 - s
 //   shared group : group = E + s,     row0 = first token,  srow = s * t_pad (row offset inside the shared region of h)
 struct TileDesc {
     int32_t group;
@@ -50,7 +51,10 @@ struct GemmArgs {
     int32_t small_tiles;       // 1: a short tail tile runs the 128/64/32-row variant
     int32_t out_fp32;          // GEMM2: 1 = y stored as fp32, 0 = bf16 (GEMM1 always stores bf16)
     int32_t k_step_on;         // 1: K offsets advance per sub-tile; 0 only for the cache-resident timing probe
-    int32_t a_tiled;           // GEMM1: routed rows of A come from a tiled x_perm (16 x 32 blocks) instead of row-major x
+    int32_t lda_bytes;         // row stride of a row-major A operand
+    int32_t kt_w;              // 1 KiB blocks per 16-row group of the packed W (its full K / 32)
+    int32_t split_rows;        // router GEMM: output rows per K-split (partial s is written at rows s*split_rows + ...)
+    int32_t a_tiled;           // A operand is in 16 x 32 blocks (else row-major): bit 0 routed tiles, bit 1 shared tiles
     int32_t t_pad;             // T rounded up to 16: rows of one shared expert's block of h
 };
 
@@ -74,7 +78,13 @@ inline int64_t max_mtiles(const moe_shape& s, int tm) {
 
 // ---- launchers (each only enqueues on `st`; returns the launch status) ----
 hipError_t launch_route(const moe_shape& s, const void* x, const void* wg, const float* bias, int32_t* idx,
-                        float* w, float* logits, hipStream_t st);
+                        float* w, float* logits, hipStream_t st);   // E <= 16: one streaming kernel
+// E > 16: uniform tile list for the router GEMM (splits x tiles of tm tokens) + the W pointer per split
+hipError_t launch_route_plan(int T, int tm, int splits, const void* wg_packed, int kt_split, PlanHeader* plan,
+                             TileDesc* descs, const void** table, hipStream_t st);
+// softmax + top-k from `splits` fp32 partial logit matrices [splits][T][ep]
+hipError_t launch_route_topk(const moe_shape& s, const float* partial, int splits, int ep, const float* bias,
+                             int32_t* idx, float* w, float* logits, hipStream_t st);
 
 constexpr int PERMUTE_CHUNK_TOKENS = 256;
 inline int permute_chunks(const moe_shape& s) { return (s.T + PERMUTE_CHUNK_TOKENS - 1) / PERMUTE_CHUNK_TOKENS; }
@@ -93,7 +103,8 @@ hipError_t ffn_gemm_init();  // one-time function attributes (dynamic LDS size)
 
 hipError_t launch_combine(const moe_shape& s, const void* y_perm, const int32_t* inv_perm, const float* w,
                           const void* y_shared, void* out, bool y_fp32, bool out_fp32, hipStream_t st);
-hipError_t launch_pack_weight(const void* in, int rows, int cols, void* out, hipStream_t st);
+// in: logical [rows = K, cols] row-major; out: packed [cols_padded x K] (cols_padded % 32 == 0, columns >= cols are zero)
+hipError_t launch_pack_weight(const void* in, int rows, int cols, int cols_padded, void* out, hipStream_t st);
 
 // Rows of the h scratch: routed rows and each shared expert's rows start on a 16-row block boundary.
 inline int64_t h_rows(const moe_shape& s) {

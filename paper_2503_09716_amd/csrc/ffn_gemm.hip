@@ -116,13 +116,14 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
     const int K = p.K, N = p.N;
     const int n0 = n_tile * BN;
     const bool shared = d.srow >= 0;
+    const int split = shared ? 0 : -1 - d.srow;   // K-split index (router GEMM only; 0 elsewhere)
     const int nseg = (!GATED && shared) ? p.nseg_shared : 1;
     const int KT = K / BK;   // sub-tiles per segment (>= 2)
     // K step in bytes: one 1 KiB block for tiled operands, 64 bytes along a row for row-major x
     const int kstep_w = p.k_step_on ? 1024 : 0;
-    // A operand: h (GEMM 2) is always tiled; GEMM 1 reads x row-major (through the gather or for
-    // shared experts) unless the caller passed a tiled x_perm for the routed rows
-    const bool a_tiled = !GATED || (p.a_tiled && d.srow < 0);
+    // A operand layout (bit 0: routed tiles, bit 1: shared tiles): h is tiled; x is row-major
+    // (read through the gather, by shared experts and by the router) unless a tiled x_perm exists
+    const bool a_tiled = ((shared ? p.a_tiled >> 1 : p.a_tiled) & 1) != 0;
     const int kstep_x = p.k_step_on ? (a_tiled ? 1024 : ROWB) : 0;
     const char* const a_base = shared ? p.a_shared : p.a_routed;
     const size_t a_seg_stride = (size_t)p.t_pad * (size_t)K * 2;   // one shared expert's block of h
@@ -148,7 +149,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
             if (!a_tiled) {
                 // x: row-major [rows, K]
                 if (!shared && p.row_token) grow = p.row_token[grow];
-                loff[i] = (uint32_t)grow * (uint32_t)(K * 2) + (uint32_t)(lpiece * 16);
+                loff[i] = (uint32_t)grow * (uint32_t)p.lda_bytes + (uint32_t)(lpiece * 16);
             } else {
                 // h: tiled; the piece this lane needs sits at slot piece ^ ((row%16)/4) of its row
                 const int rr = grow & 15;
@@ -160,7 +161,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
             const int qw = q - NQX;
             int grp = (n0 >> 4) + (GATED ? (qw & 7) : qw);
             if (grp > (N >> 4) - 1) grp = (N >> 4) - 1;
-            loff[i] = (uint32_t)grp * (uint32_t)(KT * 1024) + (uint32_t)(lane * 16);
+            loff[i] = (uint32_t)grp * (uint32_t)(p.kt_w * 1024) + (uint32_t)(lane * 16);
         }
     }
     lds_t const ring = (lds_t)lds;
@@ -254,7 +255,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
     // every other tile has one segment.  The pipeline drains and restarts between segments.
     for (int seg = 0; seg < nseg; ++seg) {
         // the descriptors span 4 GiB - 1; bounds are kept by the row clamps above
-        rs_x = uniform_rsrc(a_base + (size_t)seg * a_seg_stride);
+        rs_x = uniform_rsrc(a_base + (size_t)seg * a_seg_stride + (size_t)split * (size_t)K * 2);
         rs_w = uniform_rsrc(p.w_a[d.group + seg]);
         if (GATED) rs_u = uniform_rsrc(p.w_b[d.group]);
         koff_x = 0;
@@ -303,7 +304,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
     // lane: output row = block row (lane & 31); its 16 registers of block j are output columns
     // (block column base) + (lane >> 5) * 16 + 0..15.
     char* out = shared ? p.out_shared : p.out_routed;
-    const int orow_base = (shared ? (GATED ? d.srow : 0) : 0) + d.row0;
+    const int orow_base = (shared ? (GATED ? d.srow : 0) : split * p.split_rows) + d.row0;
 #pragma unroll
     for (int i = 0; i < TI; ++i) {
         const int r = (bx0 + i) * 32 + rl;

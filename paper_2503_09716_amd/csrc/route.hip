@@ -1,21 +1,19 @@
-// Router: fp32 gate GEMM + softmax over all experts + wavefront-level top-k.
+// Router: fp32 gate logits, softmax over all experts, wavefront-level top-k.
 // (Sec. 2 "MoE inference": the router assigns each token to its top-k experts.)
 //
-// One workgroup owns ROUTE_TOK tokens.  Phase 1 streams x and Wg through LDS in K-chunks and
-// accumulates logits with fp32 FMAs (bf16 x bf16 products are exact in fp32; a chunk-local
-// accumulator is folded into the running sum once per chunk to keep the rounding error of
-// the long sum small, which is what makes top-k agree with a correctly rounded reference
-// except at genuine near-ties).  Phase 2 parks the logits in LDS; each wavefront then takes
-// one token at a time: 64 lanes hold the token's logits, max / sum are butterfly reductions
-// and top-k is k rounds of a wave-wide arg-max (ties resolved towards the lower expert id).
+// bf16 x bf16 products are exact in fp32, so the GPU logits differ from a correctly rounded
+// reference only through the order of the fp32 additions; both paths below keep the sums short
+// enough that top-k agrees except at genuine near-ties.
+//   E <= 16 : one streaming kernel (HBM-bound): fp32 FMAs per lane, butterfly reduction.
+//   E  > 16 : the logits are a dense contraction and go through the MFMA tile routine of the
+//             grouped GEMM (x against the packed gate matrix, K cut into independent chains);
+//             route_topk_kernel then sums the partials, adds the bias and selects.
+// Selection: 64 lanes hold a token's logits, max / sum are butterfly reductions and top-k is k
+// rounds of a wave-wide arg-max on the logits (ties resolved towards the lower expert id).
 #include "common.h"
 
 namespace moe {
 namespace {
-
-constexpr int ROUTE_TOK = 32;  // tokens per workgroup
-constexpr int ROUTE_KC = 64;   // K elements per LDS chunk
-constexpr int ROUTE_LD = ROUTE_KC + 8;  // padded row length (bf16) -> 144 B rows, conflict-free 16 B reads
 
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
@@ -86,120 +84,6 @@ __device__ __forceinline__ void route_finish(const float (&v)[NV], const int lan
         if (renorm) wv = wv / wsum;
         idx_out[(size_t)t * k + lane] = my_e;
         w_out[(size_t)t * k + lane] = wv * scale;
-    }
-}
-
-// TE = experts per thread in phase 1 (thread tid%32 owns experts tid%32 + 32*i, i < TE).
-template <int TE>
-__global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ wg,
-                                                    const float* __restrict__ bias, int T, int H, int E, int k,
-                                                    int renorm, float scale, int32_t* __restrict__ idx_out,
-                                                    float* __restrict__ w_out, float* __restrict__ logits_out) {
-    constexpr int EP = TE * 32;  // padded expert count
-    __shared__ __attribute__((aligned(16))) uint16_t xs[ROUTE_TOK * ROUTE_LD];
-    __shared__ __attribute__((aligned(16))) uint16_t ws[EP * ROUTE_LD];
-    // the logits (ROUTE_TOK x EP fp32 = 128*EP bytes) reuse the Wg staging buffer (144*EP bytes)
-    float* lg = reinterpret_cast<float*>(ws);
-    static_assert(ROUTE_TOK * 4 <= ROUTE_LD * 2, "logit tile must fit in the Wg staging buffer");
-
-    const int tid = threadIdx.x;
-    const int t0 = blockIdx.x * ROUTE_TOK;
-    const int tg = tid >> 5;  // token group: tokens tg*4 .. tg*4+3
-    const int el = tid & 31;
-
-    float acc[4][TE];
-#pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int i = 0; i < TE; ++i) acc[a][i] = 0.f;
-
-    // zero the padded expert rows once (they are never written by the staging loop)
-    for (int i = tid; i < EP * ROUTE_LD; i += 256) ws[i] = 0;
-
-    for (int h0 = 0; h0 < H; h0 += ROUTE_KC) {
-        __syncthreads();
-        // stage x: ROUTE_TOK rows x 64 bf16 = 8 x 16 B per row; 256 threads, one 16 B piece each
-        {
-            const int r = tid >> 3, c = tid & 7;
-            int t = t0 + r;
-            if (t >= T) t = T - 1;
-            const uint4 v = *reinterpret_cast<const uint4*>(x + (size_t)t * H + h0 + c * 8);
-            *reinterpret_cast<uint4*>(xs + r * ROUTE_LD + c * 8) = v;
-        }
-        // stage Wg transposed: ws[e][hh] = wg[h0+hh][e]
-        for (int i = tid; i < ROUTE_KC * E; i += 256) {
-            const int hh = i / E, e = i - hh * E;
-            ws[e * ROUTE_LD + hh] = wg[(size_t)(h0 + hh) * E + e];
-        }
-        __syncthreads();
-        float part[4][TE];
-#pragma unroll
-        for (int a = 0; a < 4; ++a)
-#pragma unroll
-            for (int i = 0; i < TE; ++i) part[a][i] = 0.f;
-#pragma unroll
-        for (int k8 = 0; k8 < ROUTE_KC; k8 += 8) {
-            uint4 xv[4], wv[TE];
-#pragma unroll
-            for (int a = 0; a < 4; ++a) xv[a] = *reinterpret_cast<const uint4*>(xs + (tg * 4 + a) * ROUTE_LD + k8);
-#pragma unroll
-            for (int i = 0; i < TE; ++i) wv[i] = *reinterpret_cast<const uint4*>(ws + (el + 32 * i) * ROUTE_LD + k8);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float xl[4], xh[4], wl[TE], wh[TE];
-#pragma unroll
-                for (int a = 0; a < 4; ++a) {
-                    const uint32_t u = (&xv[a].x)[q];
-                    xl[a] = __uint_as_float(u << 16);
-                    xh[a] = __uint_as_float(u & 0xffff0000u);
-                }
-#pragma unroll
-                for (int i = 0; i < TE; ++i) {
-                    const uint32_t u = (&wv[i].x)[q];
-                    wl[i] = __uint_as_float(u << 16);
-                    wh[i] = __uint_as_float(u & 0xffff0000u);
-                }
-#pragma unroll
-                for (int a = 0; a < 4; ++a)
-#pragma unroll
-                    for (int i = 0; i < TE; ++i) {
-                        part[a][i] = fmaf(xl[a], wl[i], part[a][i]);
-                        part[a][i] = fmaf(xh[a], wh[i], part[a][i]);
-                    }
-            }
-        }
-#pragma unroll
-        for (int a = 0; a < 4; ++a)
-#pragma unroll
-            for (int i = 0; i < TE; ++i) acc[a][i] += part[a][i];
-    }
-
-    // park logits (+bias) in LDS; padded experts get -inf
-    __syncthreads();  // every thread is done reading ws
-#pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int i = 0; i < TE; ++i) {
-            const int e = el + 32 * i;
-            float v = -INFINITY;
-            if (e < E) v = acc[a][i] + (bias ? bias[e] : 0.f);
-            lg[(tg * 4 + a) * EP + e] = v;
-        }
-    __syncthreads();
-
-    // phase 2: one wavefront per token
-    constexpr int NV = (EP + 63) / 64;
-    const int lane = tid & 63, wave = tid >> 6;
-    for (int tt = wave; tt < ROUTE_TOK; tt += 4) {
-        const int t = t0 + tt;
-        if (t >= T) break;  // wave-uniform
-        float v[NV];
-#pragma unroll
-        for (int i = 0; i < NV; ++i) {
-            const int e = lane + 64 * i;
-            v[i] = (e < EP) ? lg[tt * EP + e] : -INFINITY;
-        }
-        route_finish<NV>(v, lane, t, E, k, renorm, scale, idx_out, w_out, logits_out);
     }
 }
 
@@ -276,7 +160,76 @@ __global__ __launch_bounds__(256) void route_small_kernel(const uint16_t* __rest
     }
 }
 
+// E > 16: the logits come from the grouped-GEMM tile routine (x row-major against the packed
+// gate matrix, K cut into `splits` independent accumulation chains to keep the fp32 rounding
+// error of the long sums small).  This kernel adds the partial sums in a fixed order, adds the
+// bias, and runs the wave-level softmax / top-k: one wavefront per token.
+template <int NV>
+__global__ __launch_bounds__(256) void route_topk_kernel(const float* __restrict__ partial, int splits, int T, int EP,
+                                                         int E, int k, const float* __restrict__ bias, int renorm,
+                                                         float scale, int32_t* __restrict__ idx_out,
+                                                         float* __restrict__ w_out, float* __restrict__ logits_out) {
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= T) return;  // wave-uniform
+    float v[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int e = lane + 64 * i;
+        v[i] = -INFINITY;
+        if (e < E) {
+            float a = 0.f;
+            for (int s = 0; s < splits; ++s) a += partial[((size_t)s * T + t) * EP + e];
+            v[i] = a + (bias ? bias[e] : 0.f);
+        }
+    }
+    route_finish<NV>(v, lane, t, E, k, renorm, scale, idx_out, w_out, logits_out);
+}
+
+// Tile list of the router GEMM: for every K-split s, ceil(T/tm) tiles of tm tokens; table[s]
+// points at the K-range of the packed gate matrix that split s multiplies.
+__global__ __launch_bounds__(256) void route_plan_kernel(int T, int tm, int splits, const char* wg_packed, int kt_split,
+                                                         PlanHeader* plan, TileDesc* descs, const void** table) {
+    const int per = (T + tm - 1) / tm;
+    for (int i = threadIdx.x; i < per * splits; i += 256) {
+        const int s = i / per, m = i - s * per;
+        TileDesc d;
+        d.group = s;
+        d.row0 = m * tm;
+        d.nrows = min(tm, T - m * tm);
+        d.srow = -1 - s;
+        descs[i] = d;
+    }
+    if (threadIdx.x < splits) table[threadIdx.x] = wg_packed + (size_t)threadIdx.x * kt_split * 1024;
+    if (threadIdx.x == 0) {
+        plan->n_gate_up = 0;
+        plan->n_down = per * splits;
+        plan->pad[0] = plan->pad[1] = 0;
+    }
+}
+
 }  // namespace
+
+hipError_t launch_route_plan(int T, int tm, int splits, const void* wg_packed, int kt_split, PlanHeader* plan,
+                             TileDesc* descs, const void** table, hipStream_t st) {
+    hipLaunchKernelGGL(route_plan_kernel, dim3(1), dim3(256), 0, st, T, tm, splits, (const char*)wg_packed, kt_split,
+                       plan, descs, table);
+    return hipGetLastError();
+}
+
+hipError_t launch_route_topk(const moe_shape& s, const float* partial, int splits, int ep, const float* bias,
+                             int32_t* idx, float* w, float* logits, hipStream_t st) {
+    const dim3 grid((s.T + 3) / 4), block(256);
+#define TOPK(NV_)                                                                                              \
+    hipLaunchKernelGGL(route_topk_kernel<NV_>, grid, block, 0, st, partial, splits, s.T, ep, s.E, s.top_k, bias,  \
+                       s.renormalize, s.routed_scale, idx, w, logits)
+    if (s.E <= 64) TOPK(1);
+    else if (s.E <= 128) TOPK(2);
+    else if (s.E <= 192) TOPK(3);
+    else TOPK(4);
+#undef TOPK
+    return hipGetLastError();
+}
 
 hipError_t launch_route(const moe_shape& s, const void* x, const void* wg, const float* bias, int32_t* idx,
                         float* w, float* logits, hipStream_t st) {
@@ -292,19 +245,7 @@ hipError_t launch_route(const moe_shape& s, const void* x, const void* wg, const
 #undef ROUTE_SMALL
         return hipGetLastError();
     }
-    const dim3 grid((s.T + ROUTE_TOK - 1) / ROUTE_TOK), block(256);
-    const int te = (s.E + 31) / 32;
-#define ROUTE_CASE(N)                                                                                         \
-    case N:                                                                                                   \
-        hipLaunchKernelGGL(route_kernel<N>, grid, block, 0, st, (const uint16_t*)x, (const uint16_t*)wg, bias, \
-                           s.T, s.H, s.E, s.top_k, s.renormalize, s.routed_scale, idx, w, logits);            \
-        break;
-    switch (te) {
-        ROUTE_CASE(1) ROUTE_CASE(2) ROUTE_CASE(3) ROUTE_CASE(4) ROUTE_CASE(5) ROUTE_CASE(6) ROUTE_CASE(7) ROUTE_CASE(8)
-        default: return hipErrorInvalidValue;
-    }
-#undef ROUTE_CASE
-    return hipGetLastError();
+    return hipErrorInvalidValue;  // E > 16 goes through the GEMM path (launch_route_plan / launch_route_topk)
 }
 
 }  // namespace moe

@@ -75,11 +75,11 @@ def test_fused_equals_staged_bit_for_bit(moe):
     dev = "cuda"
     idx = torch.empty((cfg.T, cfg.top_k), dtype=torch.int32, device=dev)
     w = torch.empty((cfg.T, cfg.top_k), dtype=torch.float32, device=dev)
-    moe.route(sh, gl.x, gl.wg, gl.bias, idx, w, None)
+    ws = moe.new_workspace(sh)
+    moe.route(sh, gl.x, gl.wg, gl.bias, idx, w, None, ws)
     x_perm = torch.empty((R, cfg.H), dtype=torch.bfloat16, device=dev)
     off = torch.empty(cfg.E + 1, dtype=torch.int32, device=dev)
     perm = torch.empty(R, dtype=torch.int32, device=dev); inv = torch.empty_like(perm)
-    ws = moe.new_workspace(sh)
     moe.permute(sh, gl.x, idx, x_perm, off, perm, inv, None, ws)
     h = moe.new_h_scratch(sh)
     y = torch.empty((R, cfg.H), dtype=torch.float32, device=dev)

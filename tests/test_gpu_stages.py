@@ -37,6 +37,10 @@ ROUTE_CASES = [
     ("C1", dict(T=70, H=192, E=16, top_k=4)),
     ("C3", dict(T=50, H=64, E=12, top_k=3)),
     ("C1", dict(T=9, H=1088, E=1, top_k=1)),
+    ("C4", dict(T=700, H=1024)),                  # matrix-core path, 4 K-splits
+    ("C5", dict(T=300, H=384)),                   # 2 K-splits, 160 experts padded to 160
+    ("C5", dict(T=130, H=192, E=17, top_k=5)),    # 1 K-split, 17 experts padded to 32
+    ("C3", dict(T=64, H=128, E=256, top_k=8)),
 ]
 
 
@@ -51,7 +55,8 @@ def test_route(moe, name, over):
     w = torch.empty((cfg.T, cfg.top_k), dtype=torch.float32, device="cuda")
     logits = torch.empty((cfg.T, cfg.E), dtype=torch.float32, device="cuda")
     bias = None if li.bias is None else torch.from_numpy(li.bias).cuda()
-    moe.route(shape, li.x, li.wg, bias, idx, w, logits)
+    ws = moe.new_workspace(shape)
+    moe.route(shape, li.x, li.wg, bias, idx, w, logits, ws)
     torch.cuda.synchronize()
     ref = orc.route(torch_bf16_to_u16(li.x), torch_bf16_to_u16(li.wg), li.bias, cfg.top_k, cfg.renormalize,
                     cfg.routed_scale, want_logits=True)
@@ -63,7 +68,7 @@ def test_route(moe, name, over):
         np.testing.assert_allclose(w.sum(1).cpu().numpy(), cfg.routed_scale, atol=2e-6)
     # without the optional logits output the result is the same, bit for bit
     idx2 = torch.empty_like(idx); w2 = torch.empty_like(w)
-    moe.route(shape, li.x, li.wg, bias, idx2, w2, None)
+    moe.route(shape, li.x, li.wg, bias, idx2, w2, None, ws)
     torch.cuda.synchronize()
     assert torch.equal(idx, idx2) and torch.equal(w, w2)
 
@@ -75,7 +80,8 @@ def test_route_exact_ties_pick_lowest_expert(moe):
     wg = torch.zeros((H, E), dtype=torch.bfloat16, device="cuda")
     idx = torch.empty((T, k), dtype=torch.int32, device="cuda")
     w = torch.empty((T, k), dtype=torch.float32, device="cuda")
-    moe.route(make_shape(T, H, 64, E, k, 0, False), x, wg, None, idx, w, None)
+    shape = make_shape(T, H, 64, E, k, 0, False)
+    moe.route(shape, x, wg, None, idx, w, None, moe.new_workspace(shape))
     torch.cuda.synchronize()
     assert (idx.cpu().numpy() == np.arange(k)[None, :]).all()
     np.testing.assert_allclose(w.cpu().numpy(), 1.0 / E, rtol=1e-6)
@@ -330,13 +336,16 @@ def test_error_paths(moe):
     x = torch.zeros((64, 64), dtype=torch.bfloat16, device="cuda")
     idx = torch.zeros((64, 2), dtype=torch.int32, device="cuda")
     w = torch.zeros((64, 2), dtype=torch.float32, device="cuda")
+    ws = torch.empty(1024, dtype=torch.uint8, device="cuda")
     with pytest.raises(MoeError) as e:
-        moe.route(shape, None, x, None, idx, w)
+        moe.route(shape, None, x, None, idx, w, None, ws)
     assert e.value.status == 1
     with pytest.raises(MoeError) as e:
-        moe.route(make_shape(64, 60, 64, 4, 2), x, x, None, idx, w)
+        moe.route(make_shape(64, 60, 64, 4, 2), x, x, None, idx, w, None, ws)
     assert e.value.status == 2
-    ws = torch.empty(1024, dtype=torch.uint8, device="cuda")
+    with pytest.raises(MoeError) as e:
+        moe.route(shape, x, x, None, idx, w, None, ws)
+    assert e.value.status == 3
     off = torch.zeros(5, dtype=torch.int32, device="cuda")
     perm = torch.zeros(128, dtype=torch.int32, device="cuda")
     with pytest.raises(MoeError) as e:
