@@ -53,6 +53,9 @@ def main():
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--option", action="append", default=[], help="library tuning knob key=value")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
+                    help="after the timed steps, run one plain device copy of this many MiB (a kernel of known "
+                         "HBM traffic for scaling the profiler's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -91,6 +94,12 @@ def main():
     dt = time.perf_counter() - t0
     prof = moe.profile_read()
     moe.profile_enable(False)
+    if args.calibrate_copy:
+        src = torch.empty(args.calibrate_copy << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)   # reads and writes calibrate_copy MiB each
+        torch.cuda.synchronize()
 
     ms_per_step = dt / args.steps * 1e3
     stage_ms = {s: (prof[s][0] / prof[s][1] if prof[s][1] else 0.0) for s in STAGES}

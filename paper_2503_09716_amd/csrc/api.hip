@@ -26,7 +26,7 @@ struct ProfRec {
 struct moe_ctx {
     int device = 0;
     char err[512] = {0};
-    GemmConfig gemm{2, 4, 8, 1, 1, 0, 0, -1, 0};
+    GemmConfig gemm{2, 4, 8, 1, 1, 0, 0, -1, -1, 0};
     bool y_fp32 = true;    // dtype of y_perm / y_shared
     bool out_fp32 = false; // dtype of the layer output
     // Ring of device pointer tables [3][MAX_GROUPS] (W1p, W3p, W2p), each with a pinned host
@@ -258,12 +258,15 @@ moe_status run_route(moe_ctx* c, const moe_shape& s, const void* x, const void* 
 // Rows per m-tile for one GEMM.  Tiles of 256 rows are the efficient shape (measured: the
 // 128-row shape runs at ~0.75 of their rate); 128 rows only win when a launch has so few
 // 256-row tiles that most CUs would idle in its last round.
+double expected_tiles(const moe_shape& s, int tm, int n_tiles, int nseg) {
+    return ((double)s.T * s.top_k / tm + 0.5 * s.E + (double)nseg * ((s.T + tm - 1) / tm)) * n_tiles;
+}
+
 int pick_tile_rows(const moe_shape& s, int n_tiles, int nseg) {
-    const double R = (double)s.T * s.top_k;
     double best = 0;
     int best_tm = 256;
     for (int tm : {256, 128}) {
-        const double tiles = (R / tm + 0.5 * s.E + (double)nseg * ((s.T + tm - 1) / tm)) * n_tiles;
+        const double tiles = expected_tiles(s, tm, n_tiles, nseg);
         const double rounds = (double)(int64_t)((tiles + 255) / 256);
         const double cost = rounds * tm * (tm == 128 ? 1.35 : 1.0);
         if (best == 0 || cost < best) { best = cost; best_tm = tm; }
@@ -284,9 +287,16 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     const int nt_up = (s.F + 127) / 128, nt_down = (s.H + 255) / 256;
     const int tm_up = c->gemm.tile_rows_up ? c->gemm.tile_rows_up : pick_tile_rows(s, nt_up, s.num_shared);
     const int tm_down = c->gemm.tile_rows_down ? c->gemm.tile_rows_down : pick_tile_rows(s, nt_down, s.num_shared ? 1 : 0);
+    // Short tail tiles go last when a launch has only a few rounds of tiles over the 256 CUs
+    // (its end is then a large part of its run time); with many rounds they stay interleaved.
+    const int few_rounds = 14 * 256;
+    const bool tl_up = c->gemm.tails_last >= 0 ? c->gemm.tails_last != 0
+                                               : expected_tiles(s, tm_up, nt_up, s.num_shared) < few_rounds;
+    const bool tl_down = c->gemm.tails_last >= 0 ? c->gemm.tails_last != 0
+                                                 : expected_tiles(s, tm_down, nt_down, s.num_shared ? 1 : 0) < few_rounds;
     {
         StageTimer tm(c, st, MOE_STAGE_PLAN);
-        HIP_TRY(c, launch_ffn_plan(s, offsets, tm_up, tm_down, plan, descs_up, descs_down, st));
+        HIP_TRY(c, launch_ffn_plan(s, offsets, tm_up, tm_down, tl_up, tl_down, plan, descs_up, descs_down, st));
     }
     GemmArgs a;
     memset(&a, 0, sizeof(a));
@@ -406,6 +416,7 @@ moe_status moe_set_option(moe_ctx* c, const char* key, int32_t v) {
     if (!strcmp(key, "gemm_tile_rows_up") && (v == 0 || v == 128 || v == 256)) { c->gemm.tile_rows_up = v; return MOE_OK; }
     if (!strcmp(key, "gemm_tile_rows_down") && (v == 0 || v == 128 || v == 256)) { c->gemm.tile_rows_down = v; return MOE_OK; }
     if (!strcmp(key, "x_tiled") && v >= -1 && v <= 1) { c->gemm.x_tiled = v; return MOE_OK; }
+    if (!strcmp(key, "tails_last") && v >= -1 && v <= 1) { c->gemm.tails_last = v; return MOE_OK; }
     if (!strcmp(key, "probe_k_resident") && (v == 0 || v == 1)) { c->gemm.probe_k_resident = v; return MOE_OK; }
     if (!strcmp(key, "y_fp32") && (v == 0 || v == 1)) { c->y_fp32 = v != 0; return MOE_OK; }
     if (!strcmp(key, "out_fp32") && (v == 0 || v == 1)) { c->out_fp32 = v != 0; return MOE_OK; }

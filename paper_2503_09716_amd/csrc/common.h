@@ -28,7 +28,8 @@ struct TileDesc {
 struct PlanHeader {
     int32_t n_gate_up;  // m-tiles of GEMM 1 (routed + every shared expert)
     int32_t n_down;     // m-tiles of GEMM 2 (routed + shared expert 0; shared experts are K-concatenated)
-    int32_t pad[2];
+    int32_t n_run_up;   // the first n_run_* entries of each list are in group order; short tail tiles moved
+    int32_t n_run_down; // to the end of the list (if any) follow them
 };
 
 struct GemmArgs {
@@ -67,6 +68,7 @@ struct GemmConfig {
     int tile_rows_up;      // rows per m-tile of the gate/up GEMM: 0 = choose per launch, else 128 or 256
     int tile_rows_down;    // same for the down GEMM
     int x_tiled;           // moe_layer: 1 = gather x into a tiled x_perm first, 0 = gather inside GEMM 1, -1 = choose
+    int tails_last;        // order of the m-tile lists: 1 = short tail tiles after all full tiles, 0 = in group order, -1 = choose
     int probe_k_resident;  // timing probe: every K step re-reads the first tile (results are meaningless)
 };
 
@@ -96,8 +98,8 @@ hipError_t launch_permute_gather(const moe_shape& s, const void* x, const int32_
 hipError_t launch_permute_gather_tiled(const moe_shape& s, const void* x, const int32_t* row_token, void* x_tiled,
                                        hipStream_t st);
 
-hipError_t launch_ffn_plan(const moe_shape& s, const int32_t* offsets, int tm_up, int tm_down, PlanHeader* plan,
-                           TileDesc* descs_up, TileDesc* descs_down, hipStream_t st);
+hipError_t launch_ffn_plan(const moe_shape& s, const int32_t* offsets, int tm_up, int tm_down, bool tails_last_up,
+                           bool tails_last_down, PlanHeader* plan, TileDesc* descs_up, TileDesc* descs_down, hipStream_t st);
 hipError_t launch_ffn_gemm(bool gated, const GemmArgs& a, const GemmConfig& cfg, hipStream_t st);
 hipError_t ffn_gemm_init();  // one-time function attributes (dynamic LDS size)
 

@@ -204,7 +204,8 @@ __global__ __launch_bounds__(256) void route_plan_kernel(int T, int tm, int spli
     if (threadIdx.x == 0) {
         plan->n_gate_up = 0;
         plan->n_down = per * splits;
-        plan->pad[0] = plan->pad[1] = 0;
+        plan->n_run_up = 0;
+        plan->n_run_down = per * splits;
     }
 }
 
