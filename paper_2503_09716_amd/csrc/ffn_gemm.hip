@@ -76,6 +76,27 @@ __device__ __forceinline__ void buffer_load16_to_lds(__amdgpu_buffer_rsrc_t rsrc
 #endif
 }
 
+// Descriptor over exactly [ptr, ptr + bytes): accesses at offsets >= bytes are dropped by hardware.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const void* ptr, uint32_t bytes) {
+    const uint64_t v = (uint64_t)ptr;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return __builtin_amdgcn_make_buffer_rsrc((void*)(((uint64_t)hi << 32) | lo), 0, __builtin_amdgcn_readfirstlane(bytes), 0x00020000);
+}
+
+__device__ __forceinline__ void buffer_store_b32(__amdgpu_buffer_rsrc_t rsrc, uint32_t voff, float v) {
+#if defined(__gfx950__)
+    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rsrc, voff, 0, 0);
+#endif
+}
+
+__device__ __forceinline__ void buffer_store_bf16(__amdgpu_buffer_rsrc_t rsrc, uint32_t voff, float v) {
+#if defined(__gfx950__)
+    const __bf16 b = (__bf16)v;
+    __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, b), rsrc, voff, 0, 0);
+#endif
+}
+
 // Hand-over point of the LDS ring: wait until at most N of this wave's direct-to-LDS loads
 // are still in flight (they retire in order, so everything older has landed) and until this
 // wave's own LDS reads have returned, then meet the other waves.  A bare s_barrier is used
@@ -233,7 +254,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
 #pragma unroll
             for (int m = s * G; m < (s + 1) * G; ++m) {
                 const int j = m / TI, i = m % TI;
-                acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][j], xf[buf][i], acc[j][i], 0, 0, 0);
+                if (GATED) acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][j], xf[buf][i], acc[j][i], 0, 0, 0);
+                else acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf[buf][i], wf[buf][j], acc[j][i], 0, 0, 0);
             }
             if (RD) {
 #pragma unroll
@@ -309,7 +331,6 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
     for (int i = 0; i < TI; ++i) {
         const int r = (bx0 + i) * 32 + rl;
         if (r >= d.nrows) continue;
-        char* orow = out + (size_t)(orow_base + r) * (size_t)N * 2;
         if (GATED) {
             // h is written tiled: block (row/16, col/32), row (row%16), piece slot = piece ^ ((row%16)/4)
             const int ro = orow_base + r, rr = ro & 15, sw = rr >> 2;
@@ -333,37 +354,43 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
                 *reinterpret_cast<bf16x8*>(hblk + (((c0 + 1) ^ sw) << 4)) = o1;
                 __builtin_amdgcn_sched_barrier(0);   // one block at a time: keeps accumulator reads from piling up
             }
-        } else if (p.out_fp32) {
-            orow = out + (size_t)(orow_base + r) * (size_t)N * 4;
-#pragma unroll
-            for (int j = 0; j < TJ; ++j) {
-                const int col = n0 + (bw0 + j) * 32 + g * 16;
-                if (col >= N) continue;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    f32x4 o;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = acc[j][i][q * 4 + e];
-                    *reinterpret_cast<f32x4*>(orow + (size_t)col * 4 + q * 16) = o;
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < TJ; ++j) {
-                const int col = n0 + (bw0 + j) * 32 + g * 16;
-                if (col >= N) continue;
-                bf16x8 o0, o1;
-#pragma unroll
-                for (int q = 0; q < 8; ++q) {
-                    o0[q] = (__bf16)acc[j][i][q];
-                    o1[q] = (__bf16)acc[j][i][q + 8];
-                }
-                *reinterpret_cast<bf16x8*>(orow + (size_t)col * 2) = o0;
-                *reinterpret_cast<bf16x8*>(orow + (size_t)col * 2 + 16) = o1;
-                __builtin_amdgcn_sched_barrier(0);   // one block at a time: keeps accumulator reads from piling up
-            }
         }
+    }
+    if (!GATED) {
+        // GEMM 2 / router GEMM: X is the MFMA row operand here, so register r of a lane is output
+        // row 8*(r/4) + 4*(lane/32) + r%4 of its block and all 16 registers share ONE output
+        // column: the W row this lane fed to the MFMA (LDS row lane%32 of the block, which the
+        // pack step filled with logical row ((rl/4)&1)*16 + (rl/8)*4 + rl%4).  One store
+        // instruction then writes two full 128-byte lines (fp32): 32 lanes x 4 bytes of one
+        // row.  (With W as the row operand each lane owned 64 contiguous bytes but wrote them
+        // as four 16-byte pieces, 64 partial-line requests per instruction; measured 5x slower.)
+        // Rows past the end of the group and columns past N fall outside the buffer
+        // descriptor, which spans exactly the tile's valid rows, and are dropped by hardware.
+        const int cperm = ((rl >> 2) & 1) * 16 + (rl >> 3) * 4 + (rl & 3);
+        auto store_tile = [&](auto f32_tag) __attribute__((always_inline)) {
+            constexpr bool F32 = decltype(f32_tag)::value;
+            constexpr int esz = F32 ? 4 : 2;
+            const uint32_t rowbytes = (uint32_t)N * (uint32_t)esz;
+            const __amdgpu_buffer_rsrc_t rs_o = tile_rsrc(out + (size_t)orow_base * rowbytes, (uint32_t)d.nrows * rowbytes);
+#pragma unroll
+            for (int i = 0; i < TI; ++i) {
+#pragma unroll
+                for (int j = 0; j < TJ; ++j) {
+                    const int col = n0 + (bw0 + j) * 32 + cperm;
+                    const uint32_t row = (uint32_t)((bx0 + i) * 32 + g * 4);
+                    const uint32_t voff = col < N ? row * rowbytes + (uint32_t)col * esz : 0x80000000u;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const uint32_t off = voff + (uint32_t)(8 * (r >> 2) + (r & 3)) * rowbytes;
+                        if (F32) buffer_store_b32(rs_o, off, acc[j][i][r]);
+                        else buffer_store_bf16(rs_o, off, acc[j][i][r]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);   // one block at a time: keeps accumulator reads from piling up
+                }
+            }
+        };
+        if (p.out_fp32) store_tile(T_{});
+        else store_tile(F_{});
     }
 }
 
