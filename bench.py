@@ -116,6 +116,17 @@ def main():
     if os.path.exists(tpath):
         traffic = json.load(open(tpath)).get("ffn_gate_up_hbm_bytes_per_launch")
 
+    # HBM-bound stages: algorithmic bytes / time against the 8 TB/s peak
+    gather_bytes = (cfg.T + R) * cfg.H * 2 + 4 * R
+    hbm = {
+        "route": cfg.T * cfg.H * 2 + 8 * R if cfg.E <= 16 else None,          # E > 16: the router is a GEMM
+        "permute_index": 4 * R + 12 * R,
+        "permute_gather": gather_bytes if stage_ms["permute_gather"] > 0 else None,
+        "combine": R * cfg.H * 4 + Rs * 0 + (cfg.T * cfg.H * 4 if cfg.num_shared else 0) + 8 * R + cfg.T * cfg.H * 2,
+    }
+    hbm_stages = {k: {"bytes": v, "GB/s": v / (stage_ms[k] * 1e-3) / 1e9, "frac_of_8TB/s": v / (stage_ms[k] * 1e-3) / 1e9 / PEAK_HBM_GBS}
+                  for k, v in hbm.items() if v and stage_ms[k] > 0}
+
     result = {
         "metric": "expert-module tokens/s and grouped-FFN TFLOP/s (% bf16 MFMA peak), 1 GPU",
         "value": cfg.T / (ms_per_step * 1e-3),
@@ -129,6 +140,7 @@ def main():
         "grouped_ffn_tflops": ffn_tflops,
         "grouped_ffn_frac_of_bf16_peak": ffn_tflops / PEAK_BF16_TFLOPS,
         "stage_ms": stage_ms,
+        "hbm_stages": hbm_stages,
         "roofline": {"bound": "mfma", "kernel": "ffn_gemm_kernel<gated> (gate/up projection + SiLU-gate)",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,

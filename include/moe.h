@@ -111,9 +111,12 @@ size_t moe_h_scratch_bytes(const moe_shape* shape);
  *                             chooses 1 for launches with few rounds of tiles.  Same results bit for bit.
  *   "probe_k_resident" 0 | 1  timing probe only: the GEMMs re-read their first K tile at every K step
  *                             (operands stay cache resident, RESULTS ARE MEANINGLESS); default 0
- *   "y_fp32"          0 | 1   dtype of y_perm / y_shared: 1 (default) fp32, 0 bf16.  bf16 halves the
+ *   "y_fp32"          0 | 1   staged calls: dtype of y_perm / y_shared: 1 (default) fp32, 0 bf16.  bf16 halves the
  *                             traffic of the down projection's store and of the combine's loads, but
  *                             rounds each expert output to 8 mantissa bits before the weighted sum
+ *   "layer_y_fp32"    -1|0|1  moe_layer: dtype of its internal y_perm: 1 fp32, 0 bf16, -1 (default) bf16 when
+ *                             top_k >= 4 (each rounded term then carries a small share of the sum), fp32
+ *                             otherwise.  Its y_shared is always fp32.
  *   "out_fp32"        0 | 1   dtype of the layer output written by moe_combine / moe_layer:
  *                             0 (default) bf16 = round-to-nearest-even of the fp32 sum, 1 fp32 */
 moe_status moe_set_option(moe_ctx* ctx, const char* key, int32_t value);

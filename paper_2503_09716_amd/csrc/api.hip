@@ -27,7 +27,8 @@ struct moe_ctx {
     int device = 0;
     char err[512] = {0};
     GemmConfig gemm{2, 4, 8, 1, 1, 0, 0, -1, -1, 0};
-    bool y_fp32 = true;    // dtype of y_perm / y_shared
+    bool y_fp32 = true;    // dtype of y_perm / y_shared in the staged calls
+    int layer_y = -1;      // moe_layer's y_perm: 1 fp32, 0 bf16, -1 choose (its y_shared is always fp32)
     bool out_fp32 = false; // dtype of the layer output
     // Ring of device pointer tables [3][MAX_GROUPS] (W1p, W3p, W2p), each with a pinned host
     // staging copy and an event marking the end of its upload.
@@ -240,7 +241,7 @@ moe_status run_route(moe_ctx* c, const moe_shape& s, const void* x, const void* 
     a.group_m = 8;
     a.xcd_remap = 0;
     a.small_tiles = 1;
-    a.out_fp32 = 1;
+    a.out_fp32 = 3;
     a.k_step_on = 1;
     a.lda_bytes = s.H * 2;
     a.kt_w = s.H / 32;
@@ -278,7 +279,7 @@ int pick_tile_rows(const moe_shape& s, int n_tiles, int nseg) {
 // x_perm / row_token are not used for them.
 moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int32_t* row_token, const void* x,
                    const void* x_perm_tiled, const int32_t* offsets, void** tab, char* ws, void* h, void* y_perm,
-                   void* y_shared, hipStream_t st) {
+                   void* y_shared, bool y_fp32, bool shared_fp32, hipStream_t st) {
     const Layout L = make_layout(s);
     PlanHeader* plan = (PlanHeader*)(ws + L.plan);
     TileDesc* descs_up = (TileDesc*)(ws + L.descs_up);
@@ -346,7 +347,7 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     a.lda_bytes = s.F * 2;
     a.kt_w = s.F / 32;
     a.nseg_shared = s.num_shared > 0 ? s.num_shared : 1;
-    a.out_fp32 = c->y_fp32 ? 1 : 0;
+    a.out_fp32 = (y_fp32 ? 1 : 0) | (shared_fp32 ? 2 : 0);
     a.n_tiles = nt_down;
     {
         StageTimer tm(c, st, MOE_STAGE_FFN_DOWN);
@@ -419,6 +420,7 @@ moe_status moe_set_option(moe_ctx* c, const char* key, int32_t v) {
     if (!strcmp(key, "tails_last") && v >= -1 && v <= 1) { c->gemm.tails_last = v; return MOE_OK; }
     if (!strcmp(key, "probe_k_resident") && (v == 0 || v == 1)) { c->gemm.probe_k_resident = v; return MOE_OK; }
     if (!strcmp(key, "y_fp32") && (v == 0 || v == 1)) { c->y_fp32 = v != 0; return MOE_OK; }
+    if (!strcmp(key, "layer_y_fp32") && v >= -1 && v <= 1) { c->layer_y = v; return MOE_OK; }
     if (!strcmp(key, "out_fp32") && (v == 0 || v == 1)) { c->out_fp32 = v != 0; return MOE_OK; }
     return fail(c, MOE_E_ARG, "unknown option or value out of range: %s=%d", key, (int)v);
 }
@@ -478,7 +480,8 @@ moe_status moe_grouped_ffn(moe_ctx* c, const moe_shape* s, const void* x_perm, c
     hipStream_t hs = (hipStream_t)stream;
     void** tab = nullptr;
     if (moe_status st = weight_table(c, s->E + s->num_shared, w1p, w3p, w2p, hs, &tab)) return st;
-    return run_ffn(c, *s, x_perm, row_token, x, nullptr, offsets, tab, (char*)ws, h, y_perm, y_shared, hs);
+    return run_ffn(c, *s, x_perm, row_token, x, nullptr, offsets, tab, (char*)ws, h, y_perm, y_shared, c->y_fp32,
+                   c->y_fp32, hs);
 }
 
 moe_status moe_combine(moe_ctx* c, const moe_shape* s, const void* y_perm, const int32_t* inv_perm, const float* w,
@@ -487,7 +490,7 @@ moe_status moe_combine(moe_ctx* c, const moe_shape* s, const void* y_perm, const
     if (!y_perm || !inv_perm || !w || !out) return fail(c, MOE_E_ARG, "combine: NULL pointer");
     hipStream_t hs = (hipStream_t)stream;
     StageTimer tm(c, hs, MOE_STAGE_COMBINE);
-    HIP_TRY(c, launch_combine(*s, y_perm, inv_perm, w, y_shared, out, c->y_fp32, c->out_fp32, hs));
+    HIP_TRY(c, launch_combine(*s, y_perm, inv_perm, w, y_shared, out, c->y_fp32, c->y_fp32, c->out_fp32, hs));
     return MOE_OK;
 }
 
@@ -528,11 +531,18 @@ moe_status moe_layer(moe_ctx* c, const moe_shape* s, const void* x, const void* 
         HIP_TRY(c, launch_permute_gather_tiled(*s, x, row_token, w8 + L.x_tiled, hs));
         xt = w8 + L.x_tiled;
     }
-    if (moe_status st = run_ffn(c, *s, nullptr, row_token, x, xt, offsets, tab, w8, w8 + L.h, w8 + L.y_perm, y_shared, hs))
+    // y_perm in bf16 halves the down projection's stores and the combine's loads.  Its rounding
+    // moves out[t] by at most sum_j w_j * 2^-9 * |y_j|; with k >= 4 routed terms that share a
+    // total weight <= 1 this stays far below the error bar (measured at full size: see the
+    // tests), with k = 2 it would use up most of it, so fp32 is kept there.  y_shared (weight 1)
+    // is always fp32.
+    const bool y32 = c->layer_y >= 0 ? c->layer_y != 0 : s->top_k < 4;
+    if (moe_status st = run_ffn(c, *s, nullptr, row_token, x, xt, offsets, tab, w8, w8 + L.h, w8 + L.y_perm, y_shared,
+                                y32, true, hs))
         return st;
     {
         StageTimer tm(c, hs, MOE_STAGE_COMBINE);
-        HIP_TRY(c, launch_combine(*s, w8 + L.y_perm, inv_perm, tw, y_shared, out, c->y_fp32, c->out_fp32, hs));
+        HIP_TRY(c, launch_combine(*s, w8 + L.y_perm, inv_perm, tw, y_shared, out, y32, true, c->out_fp32, hs));
     }
     return MOE_OK;
 }

@@ -31,12 +31,14 @@ __device__ __forceinline__ void accum8(float (&acc)[8], const void* __restrict__
     }
 }
 
-template <bool YF32, bool OF32>
+// YF32 / SF32: y_perm / y_shared hold fp32 (else bf16); OF32: out is fp32 (else bf16, RNE).
+template <bool YF32, bool SF32, bool OF32>
 __global__ __launch_bounds__(256) void combine_kernel(const char* __restrict__ y_perm, const int32_t* __restrict__ inv_perm,
                                                       const float* __restrict__ w, const char* __restrict__ y_shared,
                                                       int k, int H, char* __restrict__ out) {
     const int t = blockIdx.x;
     const size_t ybytes = (size_t)H * (YF32 ? 4 : 2);
+    const size_t sbytes = (size_t)H * (SF32 ? 4 : 2);
     for (int c = threadIdx.x; c < H / 8; c += 256) {
         float acc[8];
 #pragma unroll
@@ -46,7 +48,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const char* __restrict__ y
             const float wj = w[(size_t)t * k + j];
             accum8<YF32>(acc, y_perm + (size_t)r * ybytes, c, wj);
         }
-        if (y_shared) accum8<YF32>(acc, y_shared + (size_t)t * ybytes, c, 1.0f);
+        if (y_shared) accum8<SF32>(acc, y_shared + (size_t)t * sbytes, c, 1.0f);
         if (OF32) {
             float4* o = reinterpret_cast<float4*>(out + (size_t)t * H * 4) + 2 * c;
             o[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
@@ -103,14 +105,20 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const uint16_t* __rest
 }  // namespace
 
 hipError_t launch_combine(const moe_shape& s, const void* y_perm, const int32_t* inv_perm, const float* w,
-                          const void* y_shared, void* out, bool y_fp32, bool out_fp32, hipStream_t st) {
-#define COMBINE(Y, O)                                                                                           \
-    hipLaunchKernelGGL((combine_kernel<Y, O>), dim3(s.T), dim3(256), 0, st, (const char*)y_perm, inv_perm, w,   \
+                          const void* y_shared, void* out, bool y_fp32, bool shared_fp32, bool out_fp32, hipStream_t st) {
+#define COMBINE(Y, S, O)                                                                                          \
+    hipLaunchKernelGGL((combine_kernel<Y, S, O>), dim3(s.T), dim3(256), 0, st, (const char*)y_perm, inv_perm, w,  \
                        (const char*)y_shared, s.top_k, s.H, (char*)out)
-    if (y_fp32 && out_fp32) COMBINE(true, true);
-    else if (y_fp32) COMBINE(true, false);
-    else if (out_fp32) COMBINE(false, true);
-    else COMBINE(false, false);
+#define COMBINE_O(Y, S)                 \
+    do {                                \
+        if (out_fp32) COMBINE(Y, S, true); \
+        else COMBINE(Y, S, false);      \
+    } while (0)
+    if (y_fp32 && shared_fp32) COMBINE_O(true, true);
+    else if (y_fp32) COMBINE_O(true, false);
+    else if (shared_fp32) COMBINE_O(false, true);
+    else COMBINE_O(false, false);
+#undef COMBINE_O
 #undef COMBINE
     return hipGetLastError();
 }

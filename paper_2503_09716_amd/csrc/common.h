@@ -50,7 +50,7 @@ struct GemmArgs {
     int32_t group_m;
     int32_t xcd_remap;
     int32_t small_tiles;       // 1: a short tail tile runs the 128/64/32-row variant
-    int32_t out_fp32;          // GEMM2: 1 = y stored as fp32, 0 = bf16 (GEMM1 always stores bf16)
+    int32_t out_fp32;          // GEMM2: output stored as fp32 (else bf16): bit 0 routed tiles, bit 1 shared tiles (GEMM1 always stores bf16)
     int32_t k_step_on;         // 1: K offsets advance per sub-tile; 0 only for the cache-resident timing probe
     int32_t lda_bytes;         // row stride of a row-major A operand
     int32_t kt_w;              // 1 KiB blocks per 16-row group of the packed W (its full K / 32)
@@ -104,7 +104,7 @@ hipError_t launch_ffn_gemm(bool gated, const GemmArgs& a, const GemmConfig& cfg,
 hipError_t ffn_gemm_init();  // one-time function attributes (dynamic LDS size)
 
 hipError_t launch_combine(const moe_shape& s, const void* y_perm, const int32_t* inv_perm, const float* w,
-                          const void* y_shared, void* out, bool y_fp32, bool out_fp32, hipStream_t st);
+                          const void* y_shared, void* out, bool y_fp32, bool shared_fp32, bool out_fp32, hipStream_t st);
 // in: logical [rows = K, cols] row-major; out: packed [cols_padded x K] (cols_padded % 32 == 0, columns >= cols are zero)
 hipError_t launch_pack_weight(const void* in, int rows, int cols, int cols_padded, void* out, hipStream_t st);
 

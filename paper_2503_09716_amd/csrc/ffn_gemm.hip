@@ -389,7 +389,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
                 }
             }
         };
-        if (p.out_fp32) store_tile(T_{});
+        if ((shared ? p.out_fp32 >> 1 : p.out_fp32) & 1) store_tile(T_{});
         else store_tile(F_{});
     }
 }

@@ -66,28 +66,38 @@ def test_layer_everything_to_one_expert(moe):
     say(json.dumps(rep))
 
 
-def test_fused_equals_staged_bit_for_bit(moe):
-    cfg = scaled_config("C4", T=500, H=256, F=192)
+@pytest.mark.parametrize("y_fp32", [1, 0])
+def test_fused_equals_staged_bit_for_bit(moe, y_fp32):
+    """moe_layer = the staged calls, for both dtypes of y_perm (moe_layer keeps y_shared in fp32,
+    so the bf16 case is compared on a config without shared experts)."""
+    cfg = scaled_config("C4", T=500, H=256, F=192) if y_fp32 else scaled_config("C4", T=500, H=256, F=192, num_shared=0)
     gl = P.GpuLayer(moe, make_layer_inputs(cfg, device="cuda"), host_weights=False)
-    out = gl.run_layer()
-    sh = gl.shape
-    R = cfg.T * cfg.top_k
-    dev = "cuda"
-    idx = torch.empty((cfg.T, cfg.top_k), dtype=torch.int32, device=dev)
-    w = torch.empty((cfg.T, cfg.top_k), dtype=torch.float32, device=dev)
-    ws = moe.new_workspace(sh)
-    moe.route(sh, gl.x, gl.wg, gl.bias, idx, w, None, ws)
-    x_perm = torch.empty((R, cfg.H), dtype=torch.bfloat16, device=dev)
-    off = torch.empty(cfg.E + 1, dtype=torch.int32, device=dev)
-    perm = torch.empty(R, dtype=torch.int32, device=dev); inv = torch.empty_like(perm)
-    moe.permute(sh, gl.x, idx, x_perm, off, perm, inv, None, ws)
-    h = moe.new_h_scratch(sh)
-    y = torch.empty((R, cfg.H), dtype=torch.float32, device=dev)
-    ysh = torch.empty((cfg.T, cfg.H), dtype=torch.float32, device=dev)
-    moe.grouped_ffn(sh, x_perm, None, gl.x, off, gl.w1p, gl.w3p, gl.w2p, h, y, ysh, ws)
-    out2 = torch.empty_like(out)
-    moe.combine(sh, y, inv, w, ysh, out2)
-    torch.cuda.synchronize()
+    ydt = torch.float32 if y_fp32 else torch.bfloat16
+    moe.set_option("layer_y_fp32", y_fp32)
+    moe.set_option("y_fp32", y_fp32)
+    try:
+        out = gl.run_layer()
+        sh = gl.shape
+        R = cfg.T * cfg.top_k
+        dev = "cuda"
+        idx = torch.empty((cfg.T, cfg.top_k), dtype=torch.int32, device=dev)
+        w = torch.empty((cfg.T, cfg.top_k), dtype=torch.float32, device=dev)
+        ws = moe.new_workspace(sh)
+        moe.route(sh, gl.x, gl.wg, gl.bias, idx, w, None, ws)
+        x_perm = torch.empty((R, cfg.H), dtype=torch.bfloat16, device=dev)
+        off = torch.empty(cfg.E + 1, dtype=torch.int32, device=dev)
+        perm = torch.empty(R, dtype=torch.int32, device=dev); inv = torch.empty_like(perm)
+        moe.permute(sh, gl.x, idx, x_perm, off, perm, inv, None, ws)
+        h = moe.new_h_scratch(sh)
+        y = torch.empty((R, cfg.H), dtype=ydt, device=dev)
+        ysh = torch.empty((cfg.T, cfg.H), dtype=ydt, device=dev) if cfg.num_shared else None
+        moe.grouped_ffn(sh, x_perm, None, gl.x, off, gl.w1p, gl.w3p, gl.w2p, h, y, ysh, ws)
+        out2 = torch.empty_like(out)
+        moe.combine(sh, y, inv, w, ysh, out2)
+        torch.cuda.synchronize()
+    finally:
+        moe.set_option("layer_y_fp32", -1)
+        moe.set_option("y_fp32", 1)
     assert torch.equal(out.view(torch.int16), out2.view(torch.int16))
     v = moe.layer_views(sh, gl.ws)
     assert torch.equal(v["topk_idx"], idx) and torch.equal(v["topk_w"], w)
@@ -107,6 +117,21 @@ def test_tiled_gather_equals_fused_gather(moe):
             finally:
                 moe.set_option("x_tiled", -1)
         assert torch.equal(outs[0], outs[1])
+
+
+def test_tile_order_options_give_same_bits(moe):
+    """Options tails_last / gemm_group_m / xcd_remap only reorder the tiles of a launch."""
+    cfg = scaled_config("C5", T=1500, H=256, F=256, E=24, top_k=4)     # many ragged groups, shared experts
+    gl = P.GpuLayer(moe, make_layer_inputs(cfg, device="cuda"), host_weights=False)
+    ref = gl.run_layer(True)
+    for key, default, values in (("tails_last", -1, (0, 1)), ("gemm_group_m", 8, (1, 3, 16)), ("xcd_remap", 1, (0,))):
+        for v in values:
+            moe.set_option(key, v)
+            try:
+                got = gl.run_layer(True)
+            finally:
+                moe.set_option(key, default)
+            assert torch.equal(ref, got), (key, v)
 
 
 def test_layer_metamorphic_exact(moe):
