@@ -7,9 +7,9 @@
 // wavefront owns one chunk:
 //   count : per-chunk per-expert histogram
 //   scan  : per-expert exclusive prefix over chunks, then exclusive prefix over experts
-//   place : the wavefront walks its chunk 64 tokens at a time; for every expert a ballot
-//           over the 64 lanes gives each matching token its rank (popcount of lower lanes);
-//           the running per-expert cursors stay in registers (lane e%64 owns expert e)
+//   place : the wavefront walks its chunk 64 tokens at a time; a 64-bit lane mask per expert
+//           (built with integer OR in LDS) gives each token its rank (popcount of lower
+//           lanes); the running per-expert cursors stay in LDS
 //   gather: x_perm[r,:] = x[perm[r]/k,:] in 16-byte pieces, one row per wavefront pass
 #include "common.h"
 
@@ -66,73 +66,53 @@ __global__ __launch_bounds__(256) void permute_scan_kernel(int32_t* __restrict__
     }
 }
 
-// One 64-token step of the placement.  base[i] of lane l is the next free row of expert
-// i*64 + l; it lives in registers so the loop needs neither LDS nor barriers.
-template <int K>
-__device__ __forceinline__ void place_step(const int32_t* __restrict__ idx, int t, bool valid, int k_rt, int E,
-                                           int lane, int (&base)[MAX_E / 64], int32_t* __restrict__ perm,
-                                           int32_t* __restrict__ inv_perm, int32_t* __restrict__ row_token) {
-    const int k = K > 0 ? K : k_rt;
-    constexpr int KMAX = K > 0 ? K : 1;
-    int my[KMAX];
-    if (K > 0) {
-#pragma unroll
-        for (int j = 0; j < KMAX; ++j) my[j] = valid ? idx[(size_t)t * k + j] : -1;
-    }
-    const unsigned long long lt = (1ull << lane) - 1ull;
-#pragma unroll
-    for (int i = 0; i < MAX_E / 64; ++i) {
-        for (int el = 0; el < 64; ++el) {
-            const int e = i * 64 + el;
-            if (e >= E) break;
-            int hit = -1;
-            if (K > 0) {
-#pragma unroll
-                for (int j = 0; j < KMAX; ++j)
-                    if (my[j] == e) hit = j;
-            } else if (valid) {
-                for (int j = 0; j < k; ++j)
-                    if (idx[(size_t)t * k + j] == e) hit = j;
-            }
-            const unsigned long long mask = __ballot(hit >= 0);
-            if (mask == 0ull) continue;  // wave-uniform
-            const int b = __builtin_amdgcn_readlane(base[i], el);
-            if (hit >= 0) {
-                const int slot = b + __popcll(mask & lt);
-                perm[slot] = t * k + hit;
-                inv_perm[(size_t)t * k + hit] = slot;
-                if (row_token) row_token[slot] = t;
-            }
-            if (lane == el) base[i] += __popcll(mask);
-        }
-    }
-}
-
+// Placement: one wavefront per chunk, 64 tokens per step.  Every lane ORs its lane bit into a
+// 64-bit LDS mask per selected expert (an order-independent integer operation); the rank of a
+// token inside its expert's rows of this step is then the number of lower lanes in that mask,
+// which is exactly the stable token order.  The per-expert cursors live in LDS and advance by
+// the mask's population count after each step.  Work per step is O(k) per lane plus O(E/64)
+// for the cursor update, independent of how many experts the step touches.
 __global__ __launch_bounds__(64) void permute_place_kernel(const int32_t* __restrict__ idx, int T, int k, int E,
                                                            const int32_t* __restrict__ chunk_prefix,
                                                            const int32_t* __restrict__ offsets,
                                                            int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm,
                                                            int32_t* __restrict__ row_token) {
+    __shared__ unsigned long long mask[MAX_E];
+    __shared__ int cur[MAX_E];
     const int lane = threadIdx.x, chunk = blockIdx.x;
-    int base[MAX_E / 64];
-#pragma unroll
-    for (int i = 0; i < MAX_E / 64; ++i) {
-        const int e = i * 64 + lane;
-        base[i] = e < E ? offsets[e] + chunk_prefix[(size_t)chunk * E + e] : 0;
+    for (int e = lane; e < E; e += 64) {
+        cur[e] = offsets[e] + chunk_prefix[(size_t)chunk * E + e];
+        mask[e] = 0ull;
     }
+    __syncthreads();
+    const unsigned long long bit = 1ull << lane, lt = bit - 1ull;
     const int t0 = chunk * PERMUTE_CHUNK_TOKENS;
     for (int s = 0; s < PERMUTE_CHUNK_TOKENS; s += 64) {
         if (t0 + s >= T) break;
         const int t = t0 + s + lane;
         const bool valid = t < T;
-        switch (k) {
-            case 1: place_step<1>(idx, t, valid, k, E, lane, base, perm, inv_perm, row_token); break;
-            case 2: place_step<2>(idx, t, valid, k, E, lane, base, perm, inv_perm, row_token); break;
-            case 4: place_step<4>(idx, t, valid, k, E, lane, base, perm, inv_perm, row_token); break;
-            case 6: place_step<6>(idx, t, valid, k, E, lane, base, perm, inv_perm, row_token); break;
-            case 8: place_step<8>(idx, t, valid, k, E, lane, base, perm, inv_perm, row_token); break;
-            default: place_step<0>(idx, t, valid, k, E, lane, base, perm, inv_perm, row_token); break;
+        const int32_t* mine = idx + (size_t)t * k;
+        if (valid)
+            for (int j = 0; j < k; ++j) {
+                const int e = mine[j];
+                if ((unsigned)e < (unsigned)E) atomicOr(&mask[e], bit);
+            }
+        __syncthreads();
+        if (valid)
+            for (int j = 0; j < k; ++j) {
+                const int e = mine[j];
+                if ((unsigned)e >= (unsigned)E) continue;
+                const int slot = cur[e] + __popcll(mask[e] & lt);
+                perm[slot] = t * k + j;
+                inv_perm[(size_t)t * k + j] = slot;
+                if (row_token) row_token[slot] = t;
+            }
+        __syncthreads();
+        for (int e = lane; e < E; e += 64) {
+            cur[e] += __popcll(mask[e]);
+            mask[e] = 0ull;
         }
+        __syncthreads();
     }
 }
 
