@@ -532,7 +532,7 @@ moe_status moe_layer(moe_ctx* c, const moe_shape* s, const void* x, const void* 
         xt = w8 + L.x_tiled;
     }
     // y_perm in bf16 halves the down projection's stores and the combine's loads.  Its rounding
-    // moves out[t] by at most sum_j w_j * 2^-9 * |y_j|; with k >= 4 routed terms that share a
+    // moves out[t] by at most sum_j w_j * 2^-8 * |y_j|; with k >= 4 routed terms that share a
     // total weight <= 1 this stays far below the error bar (measured at full size: see the
     // tests), with k = 2 it would use up most of it, so fp32 is kept there.  y_shared (weight 1)
     // is always fp32.
