@@ -28,9 +28,8 @@
  *    logical [H,F] / [F,H] matrices (same number of bytes): the transposed matrix W[n][k]
  *    (k = contraction index) is cut into blocks of 16 rows x 32 k = 1 KiB, blocks ordered
  *    [N/16][K/32]; inside a block, row r (0..15) occupies bytes 64r..64r+63 and its 16-byte
- *    piece c (k = 8c..8c+7) sits at slot c ^ ((r/4)&3); inside every aligned 32-row block the
- *    rows are permuted: packed row 32b+rho holds logical row 32b + ((rho/4)&1)*16 +
- *    (rho/8)*4 + (rho&3).  Weights are static, so packing is not part of the timed path.
+ *    piece c (k = 8c..8c+7) sits at slot c ^ ((r/4)&3); rows keep their logical order.
+ *    Weights are static, so packing is not part of the timed path.
  *  - Limits: H % 64 == 0, F % 64 == 0, 1 <= top_k <= E <= 256, top_k <= 64,
  *    0 <= num_shared <= 8, every matrix below 4 GiB.  Other shapes: MOE_E_UNSUPPORTED.
  */

@@ -26,7 +26,7 @@ struct ProfRec {
 struct moe_ctx {
     int device = 0;
     char err[512] = {0};
-    GemmConfig gemm{2, 4, 8, 1, 1, 0, 0, -1, -1, 0};
+    GemmConfig gemm{1, 4, 8, 1, 1, 0, 0, -1, -1, 0};
     bool y_fp32 = true;    // dtype of y_perm / y_shared in the staged calls
     int layer_y = -1;      // moe_layer's y_perm: 1 fp32, 0 bf16, -1 choose (its y_shared is always fp32)
     bool out_fp32 = false; // dtype of the layer output

@@ -66,9 +66,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const char* __restrict__ y
 // out: the tiled layout the GEMM loads, i.e. the matrix W[n][k] = in[k][n] cut into blocks of
 // 16 rows x 32 k (1 KiB), blocks ordered [N/16][K/32]; inside a block, row r (0..15) occupies
 // bytes r*64..r*64+63 and its 16-byte piece c (k = 8c..8c+7) sits at slot c ^ ((r/4)&3).
-// Rows are permuted inside every aligned 32-row block: packed row 32b + rho holds logical row
-// 32b + ((rho/4)&1)*16 + (rho/8)*4 + (rho&3), the order in which the MFMA accumulator
-// registers of a lane enumerate output columns.
+// Rows keep their logical order.
 // One workgroup transposes a 32 k x 32 n patch through LDS.
 // N columns exist in `in`; blocks past them (the router pads its expert count to 32) are zero.
 __global__ __launch_bounds__(256) void pack_weight_kernel(const uint16_t* __restrict__ in, int K, int N,
@@ -88,7 +86,7 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const uint16_t* __rest
         const int r = pid >> 2, slot = pid & 3;
         const int c = slot ^ ((r >> 2) & 3);
         const int rho = grp * 16 + r;
-        const int nloc = ((rho >> 2) & 1) * 16 + (rho >> 3) * 4 + (rho & 3);
+        const int nloc = rho;
         uint16_t v[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) v[i] = patch[c * 8 + i][nloc];

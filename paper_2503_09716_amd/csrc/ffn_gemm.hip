@@ -11,8 +11,8 @@
 // wavefront then reads 1 KiB of consecutive memory (8 full 128-byte lines) instead of 16
 // half-lines from 16 distant rows, which halves the number of L1->L2 requests in flight; the
 // L1's pending-request capacity, not bandwidth, is what the row-major form ran into
-// (TCP_PENDING_STALL_CYCLES at half of all cycles).  Weight rows are additionally permuted
-// inside each 32-row block by the pack step (see below); x is read row-major through the gather.
+// (TCP_PENDING_STALL_CYCLES at half of all cycles).  x is read row-major through the gather
+// unless a tiled copy exists.
 //
 // Tile routine (one workgroup = NW wavefronts in a WM x WN grid):
 //   * macro tile: BM rows of X (256/128/64/32) x 256 rows of W (GEMM 1: 128 gate + 128 up rows,
@@ -26,13 +26,18 @@
 //     (row / 4) & 3 so the 16-byte MFMA operand reads of 16 consecutive rows fall in distinct
 //     banks.  The swizzle is applied by choosing which global piece each lane of the
 //     direct-to-LDS load fetches, since the LDS side of that load is fixed (lane * 16 bytes).
-//   * v_mfma_f32_32x32x16_bf16 with W as the row (A) operand and X as the column (B) operand:
-//     a lane's 16 accumulator registers then belong to ONE output row.  W rows are placed in
-//     LDS in the order that makes those 16 registers 16 CONSECUTIVE output columns, so the
-//     epilogue writes 16-byte stores straight from registers.
-//   * operand fragments are double-buffered in registers; the instruction stream is laid out
-//     by hand in small groups {MFMAs, one LDS read, one global load} fenced by scheduling
-//     barriers, so the matrix pipe always has independent work queued.
+//   * v_mfma_f32_16x16x32_bf16: one instruction multiplies a 16-row block of each operand over
+//     the whole sub-tile.  In a register-only loop on this workload's data it sustains 1.98
+//     PFLOP/s under the chip's power limit against 1.72 for v_mfma_f32_32x32x16_bf16 (both reach
+//     2.47 on zeros): a quarter of the accumulator traffic per multiply-add.  GEMM 1 feeds W as
+//     the row operand (a lane then owns 4 consecutive output columns of one row: 8-byte stores
+//     of bf16 h), GEMM 2 feeds X as the row operand (a lane owns one output column: a store
+//     instruction writes 4 rows x 64 contiguous bytes of fp32 y).
+//   * each operand fragment has one register copy; it is refilled from the next LDS stage
+//     right after its last use, so reads run half a sub-tile ahead of the MFMAs that need
+//     them.  The instruction stream is laid out by hand in small groups {MFMAs of one X block,
+//     one or two LDS reads, at most one global load} fenced by scheduling barriers, so the
+//     matrix pipe always has independent work queued.
 //   * ragged tails: rows past the end of a group are clamped on load and masked on store;
 //     short tails use the 128/64/32-row variants so padded MFMA work stays small.
 //
@@ -97,6 +102,23 @@ __device__ __forceinline__ void buffer_store_bf16(__amdgpu_buffer_rsrc_t rsrc, u
 #endif
 }
 
+// c += a (16 x 32, row operand) * b (32 x 16, column operand).  Written as inline assembly with
+// the accumulator tied to an AGPR quad: left to itself the register allocator (all 256 AGPRs
+// hold accumulators) routes part of them through temporaries, two to four copies per MFMA.
+// Hazards the compiler would otherwise cover: the operands come from LDS reads it still
+// tracks (s_waitcnt); an accumulator is re-used only a full sub-tile (>= 8 MFMAs) later; the
+// epilogue waits mfma_drain() before it reads accumulators.
+__device__ __forceinline__ void mfma_16x16x32(f32x4& c, const bf16x8& a, const bf16x8& b) {
+#if defined(__gfx950__)
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+#endif
+}
+__device__ __forceinline__ void mfma_drain() {
+#if defined(__gfx950__)
+    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
+#endif
+}
+
 // Hand-over point of the LDS ring: wait until at most N of this wave's direct-to-LDS loads
 // are still in flight (they retire in order, so everything older has landed) and until this
 // wave's own LDS reads have returned, then meet the other waves.  A bare s_barrier is used
@@ -126,9 +148,13 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
     constexpr int RING_STRIDE = NL * NW * 1024;    // bytes per ring stage
     static_assert(NS * RING_STRIDE <= MAX_LDS, "ring does not fit");
     constexpr int BN = GATED ? 128 : 256;    // output columns per macro tile
-    constexpr int TJH = TJ / 2;              // GATED: gate blocks per wave (= up blocks per wave)
-    constexpr int NMFMA = TI * TJ;           // MFMAs per half iteration (one K step of 16)
-    constexpr int NREAD = TI + TJ;           // LDS fragment reads per half iteration
+    constexpr int TJH = TJ / 2;              // GATED: 32-row gate blocks per wave (= up blocks per wave)
+    // The MFMA works on 16-row blocks (v_mfma_f32_16x16x32_bf16: one instruction spans a whole
+    // K sub-tile of 32).  Per wave: XB blocks of X and WB blocks of W, the latter in two halves
+    // of WBH (GEMM 1: gate blocks | up blocks).
+    constexpr int XB = 2 * TI;
+    constexpr int WB = 2 * TJ;
+    constexpr int WBH = WB / 2;
     static_assert(TJ >= 1 && (!GATED || TJ >= 2), "wave grid too wide");
 
     const int lane = threadIdx.x & 63;
@@ -198,73 +224,71 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
     };
 
     // ------------------------------------------------------------------ reader setup
-    // Lane l reads row (l & 31) of a 32-row block, logical piece kk*2 + (l >> 5), stored at
-    // slot piece ^ ((row / 4) & 3).  Block bases are multiples of 32 rows, so the swizzle term
-    // depends on the lane only.
-    const int rl = lane & 31, g = lane >> 5;
-    const int bx0 = wm * TI;
-    const int bw0 = GATED ? wn * TJH : wn * TJ;
-    uint32_t offX[2], offW[2];
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
-        const uint32_t o = (uint32_t)(rl * ROWB + ((((kk << 1) | g) ^ ((rl >> 2) & 3)) << 4));
-        offX[kk] = o + (uint32_t)(bx0 * 32 * ROWB);
-        offW[kk] = o + (uint32_t)(XBYTES + bw0 * 32 * ROWB);
-    }
+    // Lane l reads row (l & 15) of a 16-row block, logical piece l >> 4 (k = 8*(l>>4) .. +7),
+    // stored at slot piece ^ ((row / 4) & 3).  Block bases are multiples of 16 rows, so the
+    // swizzle term depends on the lane only.
+    const int rl = lane & 15, g = lane >> 4;
+    const int bx0 = wm * TI;                       // in 32-row units
+    const int bw0 = GATED ? wn * TJH : wn * TJ;    // in 32-row units
+    const uint32_t offL = (uint32_t)(rl * ROWB + ((g ^ ((rl >> 2) & 3)) << 4));
+    const uint32_t offX = offL + (uint32_t)(bx0 * 32 * ROWB);
+    const uint32_t offW = offL + (uint32_t)(XBYTES + bw0 * 32 * ROWB);
 
-    f32x16 acc[TJ][TI];
+    f32x4 acc[WB][XB];
 #pragma unroll
-    for (int j = 0; j < TJ; ++j)
+    for (int j = 0; j < WB; ++j)
 #pragma unroll
-        for (int i = 0; i < TI; ++i)
+        for (int i = 0; i < XB; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
+            for (int r = 0; r < 4; ++r) acc[j][i][r] = 0.f;
 
-    bf16x8 xf[2][TI], wf[2][TJ];   // fragment double buffer
-
-    // Fragment read number r of K step kk from the stage at `base` into buffer `buf`.
+    // Operand fragments of one sub-tile: all X blocks, and the W blocks in two halves.  wA is
+    // used by the first half of a sub-tile and refilled (from the NEXT stage) during the second;
+    // wB the other way round; X block i is refilled from the next stage right after its last
+    // MFMA of the second half.  So no fragment needs a second copy.
+    bf16x8 xf[XB], wA[WBH], wB[WBH];
     typedef __attribute__((address_space(3))) const bf16x8* frag_ptr_t;
-    auto read_frag = [&](const int stage, const int kk, const int buf, const int r) __attribute__((always_inline)) {
-        lds_t base = ring + stage * RING_STRIDE;
-        if (r < TI) {
-            xf[buf][r] = *(frag_ptr_t)(base + offX[kk] + r * 32 * ROWB);
-        } else {
-            const int j = r - TI;
-            // relative W block: GEMM 2: j; GEMM 1: gate blocks j < TJH, up blocks 4 + (j - TJH)
-            const int rel = GATED ? (j < TJH ? j : 4 + (j - TJH)) : j;
-            wf[buf][j] = *(frag_ptr_t)(base + offW[kk] + rel * 32 * ROWB);
-        }
+    auto read_x = [&](const int stage, const int i) __attribute__((always_inline)) {
+        xf[i] = *(frag_ptr_t)(ring + stage * RING_STRIDE + offX + i * 16 * ROWB);
+    };
+    // W block jj of half hf: GEMM 2: rows (hf*WBH + jj)*16; GEMM 1: gate rows jj*16 | up rows 128 + jj*16
+    auto read_w = [&](const int stage, const int hf, const int jj) __attribute__((always_inline)) {
+        const int rows = GATED ? hf * 128 + jj * 16 : (hf * WBH + jj) * 16;
+        const bf16x8 v = *(frag_ptr_t)(ring + stage * RING_STRIDE + offW + rows * ROWB);
+        if (hf == 0) wA[jj] = v;
+        else wB[jj] = v;
     };
 
-    // One half iteration: the NMFMA MFMAs of one K step from buffer `buf`, interleaved with the
-    // NREAD fragment reads of the next K step (RD) and with direct-to-LDS loads LD0..LD1-1 (LD).
-    // Laid out as NMFMA / G groups of {G MFMAs, <= 1..2 reads, <= 1 load}.
-    auto half = [&](auto rd_tag, auto ld_tag, auto ld0_tag, auto ld1_tag, const int buf, const int rd_stage,
-                    const int rd_kk, const int ld_stage) __attribute__((always_inline)) {
+    // One half of a sub-tile: XB groups, group i = the WBH MFMAs of X block i with this half's W
+    // blocks.  HF = 0 reads the second half's W blocks of the same stage; HF = 1 reads the
+    // next sub-tile's X blocks and first-half W blocks from stage `rd_stage` (RD).  Direct-to-LDS
+    // loads LD0..LD1-1 are spread over the groups (LD).
+    auto half = [&](auto hf_tag, auto rd_tag, auto ld_tag, auto ld0_tag, auto ld1_tag, const int rd_stage,
+                    const int ld_stage) __attribute__((always_inline)) {
+        constexpr int HF = decltype(hf_tag)::value;
         constexpr bool RD = decltype(rd_tag)::value;
         constexpr bool LD = decltype(ld_tag)::value;
         constexpr int LD0 = decltype(ld0_tag)::value, LD1 = decltype(ld1_tag)::value;
-        constexpr int NGRP = NMFMA >= 8 ? 8 : NMFMA;          // groups per half
-        constexpr int G = NMFMA / NGRP;                        // MFMAs per group
-        constexpr int RPG0 = (NREAD + NGRP - 1) / NGRP;
-        constexpr int RPG = RPG0 < 2 ? 2 : RPG0;               // reads per group (front-loaded)
         constexpr int NLD = LD1 - LD0;
 #pragma unroll
-        for (int s = 0; s < NGRP; ++s) {
+        for (int i = 0; i < XB; ++i) {
 #pragma unroll
-            for (int m = s * G; m < (s + 1) * G; ++m) {
-                const int j = m / TI, i = m % TI;
-                if (GATED) acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][j], xf[buf][i], acc[j][i], 0, 0, 0);
-                else acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf[buf][i], wf[buf][j], acc[j][i], 0, 0, 0);
+            for (int jj = 0; jj < WBH; ++jj) {
+                const int j = HF * WBH + jj;
+                const bf16x8 w = HF == 0 ? wA[jj] : wB[jj];
+                if (GATED) mfma_16x16x32(acc[j][i], w, xf[i]);
+                else mfma_16x16x32(acc[j][i], xf[i], w);
             }
             if (RD) {
+                if (HF == 1) read_x(rd_stage, i);
+                // the WBH W reads of this half go out with the first groups
+                constexpr int RPGW = (WBH + XB - 1) / XB;
 #pragma unroll
-                for (int r = s * RPG; r < (s + 1) * RPG && r < NREAD; ++r) read_frag(rd_stage, rd_kk, buf ^ 1, r);
+                for (int jj = i * RPGW; jj < (i + 1) * RPGW && jj < WBH; ++jj) read_w(rd_stage, 1 - HF, jj);
             }
             if (LD) {
-                // spread NLD loads over the NGRP groups
 #pragma unroll
-                for (int l = (s * NLD) / NGRP; l < ((s + 1) * NLD) / NGRP; ++l) issue_one(LD0 + l, ld_stage);
+                for (int l = (i * NLD) / XB; l < ((i + 1) * NLD) / XB; ++l) issue_one(LD0 + l, ld_stage);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -295,98 +319,95 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
         if (KT >= NS - 1) ring_sync<(NS - 2) * NL>();
         else ring_sync<0>();
 #pragma unroll
-        for (int r = 0; r < NREAD; ++r) read_frag(0, 0, 0, r);
+        for (int i = 0; i < XB; ++i) read_x(0, i);
+#pragma unroll
+        for (int jj = 0; jj < WBH; ++jj) read_w(0, 0, jj);
 
+        using H0 = std::integral_constant<int, 0>;
+        using H1 = std::integral_constant<int, 1>;
         int t = 0;
         // steady state: sub-tile t is multiplied, sub-tile t+NS-1 is loaded
         for (; t + NS - 1 < KT; ++t) {
             const int cur = t % NS, nxt = (t + 1) % NS, ld = (t + NS - 1) % NS;
-            half(T_{}, T_{}, I0{}, std::integral_constant<int, NL0>{}, 0, cur, 1, ld);
+            half(H0{}, T_{}, T_{}, I0{}, std::integral_constant<int, NL0>{}, cur, ld);
             // Sub-tile t+1 has landed once only the younger loads are outstanding.  The same
             // barrier frees stage `cur` for the loads of the NEXT iteration: its last reads were
             // issued above and have returned (lgkmcnt(0)) before any wave passes.
             ring_sync<(NS - 3) * NL + NL0>();
-            half(T_{}, T_{}, std::integral_constant<int, NL0>{}, std::integral_constant<int, NL>{}, 1, nxt, 0, ld);
+            half(H1{}, T_{}, T_{}, std::integral_constant<int, NL0>{}, std::integral_constant<int, NL>{}, nxt, ld);
             koff_x += kstep_x;
             koff_w += kstep_w;
         }
         // tail: nothing left to load; conservative waits
         for (; t < KT - 1; ++t) {
             const int cur = t % NS, nxt = (t + 1) % NS;
-            half(T_{}, F_{}, I0{}, I0{}, 0, cur, 1, 0);
+            half(H0{}, T_{}, F_{}, I0{}, I0{}, cur, 0);
             ring_sync<0>();
-            half(T_{}, F_{}, I0{}, I0{}, 1, nxt, 0, 0);
+            half(H1{}, T_{}, F_{}, I0{}, I0{}, nxt, 0);
         }
-        half(T_{}, F_{}, I0{}, I0{}, 0, t % NS, 1, 0);
+        half(H0{}, T_{}, F_{}, I0{}, I0{}, t % NS, 0);
         ring_sync<0>();    // every wave is done reading the ring before the next segment refills it
-        half(F_{}, F_{}, I0{}, I0{}, 1, 0, 0, 0);
+        half(H1{}, F_{}, F_{}, I0{}, I0{}, 0, 0);
     }
 
     // ------------------------------------------------------------------ epilogue
-    // lane: output row = block row (lane & 31); its 16 registers of block j are output columns
-    // (block column base) + (lane >> 5) * 16 + 0..15.
+    // Accumulator block (j, i) is 16 x 16; a lane holds 4 registers: the block's MFMA-row-operand
+    // index 4*(lane/16) + r and column-operand index lane%16.
+    mfma_drain();
     char* out = shared ? p.out_shared : p.out_routed;
     const int orow_base = (shared ? (GATED ? d.srow : 0) : split * p.split_rows) + d.row0;
+    if (GATED) {
+        // W is the row operand: the lane owns output row (X row) lane%16 of block i and the 4
+        // consecutive columns 4*(lane/16) .. +3 of gate block j; the up value of the same
+        // element sits in the same lane and register of block WBH + j.  h is written tiled:
+        // block (row/16, col/32), row%16 at 64 bytes each, piece slot = piece ^ ((row%16)/4);
+        // a store instruction covers 16 rows x 32 contiguous bytes.
 #pragma unroll
-    for (int i = 0; i < TI; ++i) {
-        const int r = (bx0 + i) * 32 + rl;
-        if (r >= d.nrows) continue;
-        if (GATED) {
-            // h is written tiled: block (row/16, col/32), row (row%16), piece slot = piece ^ ((row%16)/4)
+        for (int i = 0; i < XB; ++i) {
+            const int r = bx0 * 32 + i * 16 + rl;
+            const bool row_ok = r < d.nrows;
             const int ro = orow_base + r, rr = ro & 15, sw = rr >> 2;
             char* hrow = out + ((size_t)(ro >> 4) * (size_t)(N >> 5)) * 1024 + rr * 64;
 #pragma unroll
-            for (int j = 0; j < TJH; ++j) {
-                const int col = n0 + (bw0 + j) * 32 + g * 16;
-                if (col >= N) continue;
-                char* hblk = hrow + (size_t)(col >> 5) * 1024;
-                const int c0 = (col & 31) >> 3;
-                bf16x8 o0, o1;
+            for (int j = 0; j < WBH; ++j) {
+                const int col = n0 + bw0 * 32 + j * 16 + g * 4;
+                bf16x4 o;
 #pragma unroll
-                for (int q = 0; q < 8; ++q) {
-                    const float g0 = acc[j][i][q], u0 = acc[j + TJH][i][q];
-                    const float g1 = acc[j][i][q + 8], u1 = acc[j + TJH][i][q + 8];
+                for (int q = 0; q < 4; ++q) {
+                    const float gv = acc[j][i][q], uv = acc[WBH + j][i][q];
                     // silu(g) * u with the hardware reciprocal (1 ulp): far below the bf16 rounding of h
-                    o0[q] = (__bf16)(g0 * __builtin_amdgcn_rcpf(1.0f + __expf(-g0)) * u0);
-                    o1[q] = (__bf16)(g1 * __builtin_amdgcn_rcpf(1.0f + __expf(-g1)) * u1);
+                    o[q] = (__bf16)(gv * __builtin_amdgcn_rcpf(1.0f + __expf(-gv)) * uv);
                 }
-                *reinterpret_cast<bf16x8*>(hblk + ((c0 ^ sw) << 4)) = o0;
-                *reinterpret_cast<bf16x8*>(hblk + (((c0 + 1) ^ sw) << 4)) = o1;
-                __builtin_amdgcn_sched_barrier(0);   // one block at a time: keeps accumulator reads from piling up
+                if (row_ok && col < N)
+                    *reinterpret_cast<bf16x4*>(hrow + (size_t)(col >> 5) * 1024 + ((((col & 31) >> 3) ^ sw) << 4) + (col & 7) * 2) = o;
             }
+            __builtin_amdgcn_sched_barrier(0);   // one block row at a time: keeps accumulator reads from piling up
         }
-    }
-    if (!GATED) {
-        // GEMM 2 / router GEMM: X is the MFMA row operand here, so register r of a lane is output
-        // row 8*(r/4) + 4*(lane/32) + r%4 of its block and all 16 registers share ONE output
-        // column: the W row this lane fed to the MFMA (LDS row lane%32 of the block, which the
-        // pack step filled with logical row ((rl/4)&1)*16 + (rl/8)*4 + rl%4).  One store
-        // instruction then writes two full 128-byte lines (fp32): 32 lanes x 4 bytes of one
-        // row.  (With W as the row operand each lane owned 64 contiguous bytes but wrote them
-        // as four 16-byte pieces, 64 partial-line requests per instruction; measured 5x slower.)
-        // Rows past the end of the group and columns past N fall outside the buffer
-        // descriptor, which spans exactly the tile's valid rows, and are dropped by hardware.
-        const int cperm = ((rl >> 2) & 1) * 16 + (rl >> 3) * 4 + (rl & 3);
+    } else {
+        // GEMM 2 / router GEMM: X is the row operand, so the lane owns output column lane%16 of W
+        // block j and the 4 consecutive rows 4*(lane/16) .. +3 of X block i.  One store
+        // instruction writes 4 rows x 64 contiguous bytes (fp32).  Rows past the end of the
+        // group and columns past N fall outside the buffer descriptor, which spans exactly the
+        // tile's valid rows, and are dropped by hardware.
         auto store_tile = [&](auto f32_tag) __attribute__((always_inline)) {
             constexpr bool F32 = decltype(f32_tag)::value;
             constexpr int esz = F32 ? 4 : 2;
             const uint32_t rowbytes = (uint32_t)N * (uint32_t)esz;
             const __amdgpu_buffer_rsrc_t rs_o = tile_rsrc(out + (size_t)orow_base * rowbytes, (uint32_t)d.nrows * rowbytes);
 #pragma unroll
-            for (int i = 0; i < TI; ++i) {
+            for (int i = 0; i < XB; ++i) {
 #pragma unroll
-                for (int j = 0; j < TJ; ++j) {
-                    const int col = n0 + (bw0 + j) * 32 + cperm;
-                    const uint32_t row = (uint32_t)((bx0 + i) * 32 + g * 4);
+                for (int j = 0; j < WB; ++j) {
+                    const int col = n0 + bw0 * 32 + j * 16 + rl;
+                    const uint32_t row = (uint32_t)(bx0 * 32 + i * 16 + g * 4);
                     const uint32_t voff = col < N ? row * rowbytes + (uint32_t)col * esz : 0x80000000u;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const uint32_t off = voff + (uint32_t)(8 * (r >> 2) + (r & 3)) * rowbytes;
-                        if (F32) buffer_store_b32(rs_o, off, acc[j][i][r]);
-                        else buffer_store_bf16(rs_o, off, acc[j][i][r]);
+                    for (int r = 0; r < 4; ++r) {
+                        if (F32) buffer_store_b32(rs_o, voff + (uint32_t)r * rowbytes, acc[j][i][r]);
+                        else buffer_store_bf16(rs_o, voff + (uint32_t)r * rowbytes, acc[j][i][r]);
                     }
-                    __builtin_amdgcn_sched_barrier(0);   // one block at a time: keeps accumulator reads from piling up
                 }
+                __builtin_amdgcn_sched_barrier(0);   // one block row at a time
             }
         };
         if ((shared ? p.out_fp32 >> 1 : p.out_fp32) & 1) store_tile(T_{});

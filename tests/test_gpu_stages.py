@@ -172,7 +172,7 @@ def run_ffn_stage(moe, cfg, idx_h, wave_rows=2, small_tiles=1, use_row_token=Fal
     return y, ysh, perm.cpu().numpy(), off.cpu().numpy(), li
 
 
-DEFAULT_WAVES, DEFAULT_WAVE_ROWS = 4, 2
+DEFAULT_WAVES, DEFAULT_WAVE_ROWS = 4, 1
 
 FFN_CASES = [
     # name, overrides, skew, waves, wave_rows, small_tiles, row_token
@@ -311,8 +311,7 @@ def packed_reference(w: np.ndarray) -> np.ndarray:
     K, N = w.shape
     out = np.empty(K * N, w.dtype)
     for n in range(N):
-        b, rho = divmod(n, 32)          # which logical row does packed row n hold?
-        src = 32 * b + ((rho // 4) & 1) * 16 + (rho // 8) * 4 + (rho & 3)
+        src = n                         # rows keep their logical order
         g, r = divmod(n, 16)
         for kt in range(K // 32):
             base = (g * (K // 32) + kt) * 512
