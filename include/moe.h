@@ -194,6 +194,30 @@ moe_status moe_layer(moe_ctx* ctx, const moe_shape* shape, const void* x_bf16, c
                      const void* const* w2p, void* out, void* workspace, size_t workspace_bytes,
                      void* hip_stream);
 
+/* moe_layer with the expert weights in HOST memory (Sec. 4.2: experts are executed one after
+ * another while the next expert's weights are prefetched into a second buffer; App. A: only
+ * experts that received tokens are fetched).  Experts are taken in groups of
+ * `experts_per_group` consecutive non-empty experts; group g is copied into staging slot
+ * g % num_slots with hipMemcpyAsync on a stream the context owns while the GEMMs of earlier
+ * groups run on `hip_stream`; events hand the slots back and forth.  The shared experts form
+ * the last group.  Same kernels and same results as moe_layer, bit for bit.
+ *   host_w1p / host_w3p / host_w2p: host arrays of E+num_shared HOST pointers to packed
+ *   matrices (H*F bf16 each, moe_pack_weight layout), in pinned memory for the copies to overlap
+ *   slots: device buffer of num_slots * slot_bytes bytes; a slot must hold
+ *   max(experts_per_group, num_shared) experts, 3*H*F*2 bytes each; num_slots in 2..8
+ * The call SYNCHRONISES hip_stream once (it needs the per-expert row counts on the host to
+ * decide what to fetch); everything after that is enqueued asynchronously.
+ * Errors: as moe_layer; MOE_E_ARG for a slot that is too small. */
+moe_status moe_layer_streamed(moe_ctx* ctx, const moe_shape* shape, const void* x_bf16, const void* wg_bf16,
+                              const float* gate_bias, const void* const* host_w1p, const void* const* host_w3p,
+                              const void* const* host_w2p, void* slots, size_t slot_bytes, int32_t num_slots,
+                              int32_t experts_per_group, void* out, void* workspace, size_t workspace_bytes,
+                              void* hip_stream);
+
+/* Counters of the last moe_layer_streamed call: bytes copied host -> device, expert groups run,
+ * experts skipped because they had no rows.  Any out-pointer may be NULL. */
+moe_status moe_stream_stats(const moe_ctx* ctx, uint64_t* bytes_copied, int32_t* groups, int32_t* experts_skipped);
+
 /* Device pointers into a workspace last used by moe_layer with this shape, for inspection:
  * topk_idx [T,k] int32, topk_w [T,k] fp32, expert_offsets [E+1] int32, inv_perm [T*k] int32.
  * Any out-pointer may be NULL. */

@@ -20,6 +20,7 @@ STAGES = ["route", "permute_index", "permute_gather", "plan", "ffn_gate_up", "ff
 EXPORTS = [
     "moe_create", "moe_destroy", "moe_last_error", "moe_workspace_bytes", "moe_h_scratch_bytes", "moe_set_option", "moe_pack_weight",
     "moe_route", "moe_permute", "moe_grouped_ffn", "moe_combine", "moe_layer", "moe_layer_views",
+    "moe_layer_streamed", "moe_stream_stats",
     "moe_profile_enable", "moe_profile_read",
 ]
 
@@ -66,6 +67,9 @@ def load_library():
     lib.moe_grouped_ffn.argtypes = [C.c_void_p, sp, vp, i32p, vp, i32p, tab, tab, tab, vp, vp, vp, vp, C.c_size_t, vp]
     lib.moe_combine.argtypes = [C.c_void_p, sp, vp, i32p, f32p, vp, vp, vp]
     lib.moe_layer.argtypes = [C.c_void_p, sp, vp, vp, f32p, tab, tab, tab, vp, vp, C.c_size_t, vp]
+    lib.moe_layer_streamed.argtypes = [C.c_void_p, sp, vp, vp, f32p, tab, tab, tab, vp, C.c_size_t, C.c_int32, C.c_int32,
+                                       vp, vp, C.c_size_t, vp]
+    lib.moe_stream_stats.argtypes = [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.moe_layer_views.argtypes = [sp, vp, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
                                     C.POINTER(C.c_void_p)]
     lib.moe_profile_enable.argtypes = [C.c_void_p, C.c_int32]
@@ -188,6 +192,25 @@ class Moe:
         t1, t3, t2 = tables if tables is not None else (_table(w1p), _table(w3p), _table(w2p))
         self._check(self.lib.moe_layer(self.h, C.byref(shape), _ptr(x), _ptr(wg), _ptr(bias), t1, t3, t2,
                                        _ptr(out), _ptr(workspace), workspace.numel(), _stream()))
+
+    def layer_streamed(self, shape, x, wg, bias, host_w1p, host_w3p, host_w2p, slots, num_slots, experts_per_group,
+                       out, workspace):
+        """Expert weights in pinned HOST tensors (packed layout); `slots` is a device byte buffer
+        cut into num_slots equal staging slots."""
+        def host_table(ws):
+            for w in ws:
+                assert (not w.is_cuda) and w.is_pinned() and w.is_contiguous(), "pinned host tensor required"
+            return (C.c_void_p * len(ws))(*[w.data_ptr() for w in ws])
+        slot_bytes = (slots.numel() * slots.element_size() // num_slots) & ~255
+        self._check(self.lib.moe_layer_streamed(self.h, C.byref(shape), _ptr(x), _ptr(wg), _ptr(bias),
+                                                host_table(host_w1p), host_table(host_w3p), host_table(host_w2p),
+                                                _ptr(slots), slot_bytes, num_slots, experts_per_group, _ptr(out),
+                                                _ptr(workspace), workspace.numel(), _stream()))
+
+    def stream_stats(self):
+        b, g, k = C.c_uint64(), C.c_int32(), C.c_int32()
+        self._check(self.lib.moe_stream_stats(self.h, C.byref(b), C.byref(g), C.byref(k)))
+        return {"bytes_copied": b.value, "groups": g.value, "experts_skipped": k.value}
 
     def tables(self, w1p, w3p, w2p):
         """Pre-marshalled pointer tables, so a timed loop does not rebuild them per call."""

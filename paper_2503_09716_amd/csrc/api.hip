@@ -15,6 +15,7 @@ namespace {
 constexpr int TABLE_SLOTS = 8;
 constexpr int MAX_GROUPS = 256;
 constexpr int PROF_MAX = 8192;
+constexpr int MAX_SLOTS = 8;
 
 struct ProfRec {
     int stage;
@@ -39,6 +40,13 @@ struct moe_ctx {
     int tab_cur = -1;
     int tab_n = 0;
     std::vector<const void*> tab_shadow;  // contents of slot tab_cur
+    // streamed weights: copy stream, slot hand-over events, pinned copy of expert_offsets, counters
+    hipStream_t copy_stream = nullptr;
+    hipEvent_t slot_ready[MAX_SLOTS] = {nullptr};
+    hipEvent_t slot_free[MAX_SLOTS] = {nullptr};
+    int32_t* h_offsets = nullptr;
+    uint64_t stream_bytes = 0;
+    int stream_groups = 0, stream_skipped = 0;
     // profiling
     bool prof = false;
     std::vector<ProfRec> recs;
@@ -275,11 +283,21 @@ int pick_tile_rows(const moe_shape& s, int n_tiles, int nseg) {
     return best_tm;
 }
 
+// Which groups one pass of the two GEMMs covers (streamed weights run several passes), and how
+// many m-tiles it can have at most (0 = the bound for any routing).
+struct FfnPass {
+    int e_lo, e_hi;
+    bool shared_on;
+    int mtiles_up, mtiles_down;
+};
+
 // x_perm_tiled: when non-null, the routed rows of GEMM 1 are read from it (tiled layout) and
 // x_perm / row_token are not used for them.
 moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int32_t* row_token, const void* x,
                    const void* x_perm_tiled, const int32_t* offsets, void** tab, char* ws, void* h, void* y_perm,
-                   void* y_shared, bool y_fp32, bool shared_fp32, hipStream_t st) {
+                   void* y_shared, bool y_fp32, bool shared_fp32, hipStream_t st, const FfnPass* pass = nullptr) {
+    const FfnPass all{0, s.E, true, 0, 0};
+    const FfnPass& ps = pass ? *pass : all;
     const Layout L = make_layout(s);
     PlanHeader* plan = (PlanHeader*)(ws + L.plan);
     TileDesc* descs_up = (TileDesc*)(ws + L.descs_up);
@@ -297,7 +315,8 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
                                                  : expected_tiles(s, tm_down, nt_down, s.num_shared ? 1 : 0) < few_rounds;
     {
         StageTimer tm(c, st, MOE_STAGE_PLAN);
-        HIP_TRY(c, launch_ffn_plan(s, offsets, tm_up, tm_down, tl_up, tl_down, plan, descs_up, descs_down, st));
+        HIP_TRY(c, launch_ffn_plan(s, offsets, tm_up, tm_down, tl_up, tl_down, ps.e_lo, ps.e_hi, ps.shared_on, plan,
+                                   descs_up, descs_down, st));
     }
     GemmArgs a;
     memset(&a, 0, sizeof(a));
@@ -312,7 +331,7 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     a.split_rows = 0;
     // GEMM 1: [rows, H] x W1p/W3p [F, H] -> h [rows, F]
     a.descs = descs_up;
-    a.max_mtiles = (int)max_mtiles(s, tm_up);
+    a.max_mtiles = ps.mtiles_up > 0 ? ps.mtiles_up : (int)max_mtiles(s, tm_up);
     a.a_routed = (const char*)(x_perm_tiled ? x_perm_tiled : (row_token ? x : x_perm));
     a.a_shared = (const char*)x;
     a.row_token = x_perm_tiled ? nullptr : row_token;
@@ -333,7 +352,7 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     }
     // GEMM 2: h [rows, F] x W2p [H, F] -> y [rows, H]
     a.descs = descs_down;
-    a.max_mtiles = (int)max_mtiles(s, tm_down);
+    a.max_mtiles = ps.mtiles_down > 0 ? ps.mtiles_down : (int)max_mtiles(s, tm_down);
     a.a_routed = (const char*)h;
     a.a_shared = (const char*)h + Rpad * s.F * 2;
     a.row_token = nullptr;
@@ -356,6 +375,57 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     return MOE_OK;
 }
 
+// Route, permutation indices and (for wide experts) the tiled gather of moe_layer; the pointers
+// into the workspace that the rest of the layer uses.
+struct LayerFront {
+    int32_t *topk_idx, *offsets, *perm, *inv_perm, *row_token;
+    float* topk_w;
+    const void* x_tiled;   // nullptr: the gather is fused into GEMM 1's loads
+    void *h, *y_perm, *y_shared;
+    bool y32;              // dtype of y_perm
+};
+
+moe_status run_front(moe_ctx* c, const moe_shape& s, const void* x, const void* wg, const float* bias, char* w8,
+                     hipStream_t hs, LayerFront* f) {
+    const Layout L = make_layout(s);
+    f->topk_idx = (int32_t*)(w8 + L.topk_idx);
+    f->topk_w = (float*)(w8 + L.topk_w);
+    f->offsets = (int32_t*)(w8 + L.offsets);
+    f->perm = (int32_t*)(w8 + L.perm);
+    f->inv_perm = (int32_t*)(w8 + L.inv_perm);
+    f->row_token = (int32_t*)(w8 + L.row_token);
+    f->h = w8 + L.h;
+    f->y_perm = w8 + L.y_perm;
+    f->y_shared = s.num_shared > 0 ? (void*)(w8 + L.y_shared) : nullptr;
+    {
+        StageTimer tm(c, hs, MOE_STAGE_ROUTE);
+        if (moe_status st = run_route(c, s, x, wg, bias, f->topk_idx, f->topk_w, nullptr, w8, hs)) return st;
+    }
+    {
+        StageTimer tm(c, hs, MOE_STAGE_PERMUTE_INDEX);
+        HIP_TRY(c, launch_permute_index(s, f->topk_idx, (int32_t*)(w8 + L.chunk_counts), f->offsets, f->perm, f->inv_perm,
+                                        f->row_token, hs));
+    }
+    // The gather is either fused into GEMM 1's loads (row-major x, 64-byte pieces from 16 distant
+    // rows per load) or done once into a tiled x_perm (one extra pass over T*k*H*2 bytes, after
+    // which GEMM 1 loads whole 1 KiB blocks).  The extra pass pays off when each x row is re-read
+    // by many n-tiles, i.e. for wide experts.
+    const bool tiled = c->gemm.x_tiled == 1 || (c->gemm.x_tiled < 0 && s.F >= 4096);
+    f->x_tiled = nullptr;
+    if (tiled) {
+        StageTimer tm(c, hs, MOE_STAGE_PERMUTE_GATHER);
+        HIP_TRY(c, launch_permute_gather_tiled(s, x, f->row_token, w8 + L.x_tiled, hs));
+        f->x_tiled = w8 + L.x_tiled;
+    }
+    // y_perm in bf16 halves the down projection's stores and the combine's loads.  Its rounding
+    // moves out[t] by at most sum_j w_j * 2^-8 * |y_j|; with k >= 4 routed terms that share a
+    // total weight <= 1 this stays far below the error bar (measured at full size: see the
+    // tests), with k = 2 it would use up most of it, so fp32 is kept there.  y_shared (weight 1)
+    // is always fp32.
+    f->y32 = c->layer_y >= 0 ? c->layer_y != 0 : s.top_k < 4;
+    return MOE_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -368,6 +438,11 @@ moe_status moe_create(moe_ctx** out, int device) {
     c->device = device;
     c->tab_shadow.assign(3 * MAX_GROUPS, nullptr);
     bool ok = ffn_gemm_init() == hipSuccess;
+    ok = ok && hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking) == hipSuccess &&
+         hipHostMalloc((void**)&c->h_offsets, (MAX_GROUPS + 1) * sizeof(int32_t), hipHostMallocDefault) == hipSuccess;
+    for (int i = 0; i < MAX_SLOTS && ok; ++i)
+        ok = hipEventCreateWithFlags(&c->slot_ready[i], hipEventDisableTiming) == hipSuccess &&
+             hipEventCreateWithFlags(&c->slot_free[i], hipEventDisableTiming) == hipSuccess;
     for (int i = 0; i < TABLE_SLOTS && ok; ++i) {
         ok = hipMalloc((void**)&c->d_tab[i], 3 * MAX_GROUPS * sizeof(void*)) == hipSuccess &&
              hipHostMalloc((void**)&c->h_tab[i], 3 * MAX_GROUPS * sizeof(void*), hipHostMallocDefault) == hipSuccess &&
@@ -387,6 +462,12 @@ void moe_destroy(moe_ctx* c) {
         if (c->h_tab[i]) (void)hipHostFree(c->h_tab[i]);
         if (c->tab_done[i]) (void)hipEventDestroy(c->tab_done[i]);
     }
+    for (int i = 0; i < MAX_SLOTS; ++i) {
+        if (c->slot_ready[i]) (void)hipEventDestroy(c->slot_ready[i]);
+        if (c->slot_free[i]) (void)hipEventDestroy(c->slot_free[i]);
+    }
+    if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
+    if (c->h_offsets) (void)hipHostFree(c->h_offsets);
     for (auto& r : c->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     for (auto e : c->pool) (void)hipEventDestroy(e);
     delete c;
@@ -503,47 +584,106 @@ moe_status moe_layer(moe_ctx* c, const moe_shape* s, const void* x, const void* 
     hipStream_t hs = (hipStream_t)stream;
     void** tab = nullptr;
     if (moe_status st = weight_table(c, s->E + s->num_shared, w1p, w3p, w2p, hs, &tab)) return st;
-    const Layout L = make_layout(*s);
-    char* w8 = (char*)ws;
-    int32_t* idx = (int32_t*)(w8 + L.topk_idx);
-    float* tw = (float*)(w8 + L.topk_w);
-    int32_t* offsets = (int32_t*)(w8 + L.offsets);
-    int32_t* perm = (int32_t*)(w8 + L.perm);
-    int32_t* inv_perm = (int32_t*)(w8 + L.inv_perm);
-    int32_t* row_token = (int32_t*)(w8 + L.row_token);
-    void* y_shared = s->num_shared > 0 ? (void*)(w8 + L.y_shared) : nullptr;
-    {
-        StageTimer tm(c, hs, MOE_STAGE_ROUTE);
-        if (moe_status st = run_route(c, *s, x, wg, bias, idx, tw, nullptr, w8, hs)) return st;
-    }
-    {
-        StageTimer tm(c, hs, MOE_STAGE_PERMUTE_INDEX);
-        HIP_TRY(c, launch_permute_index(*s, idx, (int32_t*)(w8 + L.chunk_counts), offsets, perm, inv_perm, row_token, hs));
-    }
-    // The gather is either fused into GEMM 1's loads (row-major x, 64-byte pieces from 16 distant
-    // rows per load) or done once into a tiled x_perm (one extra pass over T*k*H*2 bytes, after
-    // which GEMM 1 loads whole 1 KiB blocks).  The extra pass pays off when each x row is re-read
-    // by many n-tiles, i.e. for wide experts.
-    const bool tiled = c->gemm.x_tiled == 1 || (c->gemm.x_tiled < 0 && s->F >= 4096);
-    const void* xt = nullptr;
-    if (tiled) {
-        StageTimer tm(c, hs, MOE_STAGE_PERMUTE_GATHER);
-        HIP_TRY(c, launch_permute_gather_tiled(*s, x, row_token, w8 + L.x_tiled, hs));
-        xt = w8 + L.x_tiled;
-    }
-    // y_perm in bf16 halves the down projection's stores and the combine's loads.  Its rounding
-    // moves out[t] by at most sum_j w_j * 2^-8 * |y_j|; with k >= 4 routed terms that share a
-    // total weight <= 1 this stays far below the error bar (measured at full size: see the
-    // tests), with k = 2 it would use up most of it, so fp32 is kept there.  y_shared (weight 1)
-    // is always fp32.
-    const bool y32 = c->layer_y >= 0 ? c->layer_y != 0 : s->top_k < 4;
-    if (moe_status st = run_ffn(c, *s, nullptr, row_token, x, xt, offsets, tab, w8, w8 + L.h, w8 + L.y_perm, y_shared,
-                                y32, true, hs))
+    LayerFront f;
+    if (moe_status st = run_front(c, *s, x, wg, bias, (char*)ws, hs, &f)) return st;
+    if (moe_status st = run_ffn(c, *s, nullptr, f.row_token, x, f.x_tiled, f.offsets, tab, (char*)ws, f.h, f.y_perm,
+                                f.y_shared, f.y32, true, hs))
         return st;
     {
         StageTimer tm(c, hs, MOE_STAGE_COMBINE);
-        HIP_TRY(c, launch_combine(*s, w8 + L.y_perm, inv_perm, tw, y_shared, out, y32, true, c->out_fp32, hs));
+        HIP_TRY(c, launch_combine(*s, f.y_perm, f.inv_perm, f.topk_w, f.y_shared, out, f.y32, true, c->out_fp32, hs));
     }
+    return MOE_OK;
+}
+
+moe_status moe_layer_streamed(moe_ctx* c, const moe_shape* s, const void* x, const void* wg, const float* bias,
+                              const void* const* hw1, const void* const* hw3, const void* const* hw2, void* slots,
+                              size_t slot_bytes, int32_t num_slots, int32_t per_group, void* out, void* ws,
+                              size_t ws_bytes, void* stream) {
+    if (moe_status st = check_common(c, s)) return st;
+    if (!x || !wg || !out || !slots || !hw1 || !hw3 || !hw2) return fail(c, MOE_E_ARG, "layer_streamed: NULL pointer");
+    if (moe_status st = check_ws(c, s, ws, ws_bytes)) return st;
+    const int E = s->E, Ns = s->num_shared;
+    const size_t mat_bytes = (size_t)s->H * s->F * 2, expert_bytes = 3 * mat_bytes;
+    if (num_slots < 2 || num_slots > MAX_SLOTS) return fail(c, MOE_E_ARG, "layer_streamed: num_slots must be 2..%d", MAX_SLOTS);
+    if (per_group < 1 || per_group > E) return fail(c, MOE_E_ARG, "layer_streamed: experts_per_group must be 1..E");
+    const int cap = per_group > Ns ? per_group : Ns;
+    if (slot_bytes < (size_t)cap * expert_bytes || ((uintptr_t)slots & 255) || (slot_bytes & 255))
+        return fail(c, MOE_E_ARG, "layer_streamed: a slot needs %zu bytes (256-byte aligned), got %zu", (size_t)cap * expert_bytes, slot_bytes);
+    for (int e = 0; e < E + Ns; ++e)
+        if (!hw1[e] || !hw3[e] || !hw2[e]) return fail(c, MOE_E_ARG, "layer_streamed: host weight pointer %d is NULL", e);
+    hipStream_t hs = (hipStream_t)stream;
+    LayerFront f;
+    if (moe_status st = run_front(c, *s, x, wg, bias, (char*)ws, hs, &f)) return st;
+    // the per-expert row counts decide what is fetched: one synchronising read-back
+    HIP_TRY(c, hipMemcpyAsync(c->h_offsets, f.offsets, (size_t)(E + 1) * sizeof(int32_t), hipMemcpyDeviceToHost, hs));
+    HIP_TRY(c, hipStreamSynchronize(hs));
+    c->stream_bytes = 0;
+    c->stream_groups = 0;
+    c->stream_skipped = 0;
+
+    // groups: runs of up to per_group non-empty routed experts (a group spans [lo, hi) and the
+    // empty experts inside it are neither copied nor given tiles), then the shared experts
+    struct Group { int lo, hi; bool shared; };
+    std::vector<Group> groups;
+    for (int e = 0; e < E;) {
+        while (e < E && c->h_offsets[e + 1] == c->h_offsets[e]) { ++e; ++c->stream_skipped; }
+        if (e >= E) break;
+        int lo = e, n = 0;
+        while (e < E && n < per_group) {
+            if (c->h_offsets[e + 1] > c->h_offsets[e]) ++n;
+            else ++c->stream_skipped;
+            ++e;
+        }
+        groups.push_back({lo, e, false});
+    }
+    if (Ns > 0) groups.push_back({E, E, true});
+
+    std::vector<const void*> t1(E + Ns), t3(E + Ns), t2(E + Ns);
+    for (size_t g = 0; g < groups.size(); ++g) {
+        const Group& G = groups[g];
+        const int slot = (int)(g % (size_t)num_slots);
+        char* base = (char*)slots + (size_t)slot * slot_bytes;
+        if (g >= (size_t)num_slots) HIP_TRY(c, hipStreamWaitEvent(c->copy_stream, c->slot_free[slot], 0));
+        // every table entry must be a valid pointer; experts outside the group get no tiles
+        for (int e = 0; e < E + Ns; ++e) { t1[e] = base; t3[e] = base; t2[e] = base; }
+        int member = 0, mt = 0;
+        const int e0 = G.shared ? E : G.lo, e1 = G.shared ? E + Ns : G.hi;
+        for (int e = e0; e < e1; ++e) {
+            const int rows = e < E ? c->h_offsets[e + 1] - c->h_offsets[e] : s->T;
+            if (rows == 0) continue;
+            char* dst = base + (size_t)member * expert_bytes;
+            HIP_TRY(c, hipMemcpyAsync(dst, hw1[e], mat_bytes, hipMemcpyHostToDevice, c->copy_stream));
+            HIP_TRY(c, hipMemcpyAsync(dst + mat_bytes, hw3[e], mat_bytes, hipMemcpyHostToDevice, c->copy_stream));
+            HIP_TRY(c, hipMemcpyAsync(dst + 2 * mat_bytes, hw2[e], mat_bytes, hipMemcpyHostToDevice, c->copy_stream));
+            t1[e] = dst; t3[e] = dst + mat_bytes; t2[e] = dst + 2 * mat_bytes;
+            c->stream_bytes += expert_bytes;
+            mt += (rows + 127) / 128;
+            ++member;
+        }
+        HIP_TRY(c, hipEventRecord(c->slot_ready[slot], c->copy_stream));
+        HIP_TRY(c, hipStreamWaitEvent(hs, c->slot_ready[slot], 0));
+        void** tab = nullptr;
+        if (moe_status st = weight_table(c, E + Ns, t1.data(), t3.data(), t2.data(), hs, &tab)) return st;
+        const FfnPass pass{G.shared ? 0 : G.lo, G.shared ? 0 : G.hi, G.shared, mt, G.shared ? (s->T + 127) / 128 : mt};
+        if (moe_status st = run_ffn(c, *s, nullptr, f.row_token, x, f.x_tiled, f.offsets, tab, (char*)ws, f.h, f.y_perm,
+                                    f.y_shared, f.y32, true, hs, &pass))
+            return st;
+        HIP_TRY(c, hipEventRecord(c->slot_free[slot], hs));
+        ++c->stream_groups;
+    }
+    {
+        StageTimer tm(c, hs, MOE_STAGE_COMBINE);
+        HIP_TRY(c, launch_combine(*s, f.y_perm, f.inv_perm, f.topk_w, f.y_shared, out, f.y32, true, c->out_fp32, hs));
+    }
+    return MOE_OK;
+}
+
+moe_status moe_stream_stats(const moe_ctx* c, uint64_t* bytes, int32_t* groups, int32_t* skipped) {
+    if (!c) return MOE_E_ARG;
+    if (bytes) *bytes = c->stream_bytes;
+    if (groups) *groups = c->stream_groups;
+    if (skipped) *skipped = c->stream_skipped;
     return MOE_OK;
 }
 

@@ -505,7 +505,7 @@ __global__ __launch_bounds__(512, 2) void ffn_gemm_kernel8(const GemmArgs p) {
 // on its smallest work items.  n_run_* = number of entries listed in group order.
 __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict__ offsets, int T, int t_pad, int E, int Ns,
                                                        int tm_up, int tm_down, int tails_last_up, int tails_last_down,
-                                                       PlanHeader* __restrict__ plan,
+                                                       int e_lo, int e_hi, int shared_on, PlanHeader* __restrict__ plan,
                                                        TileDesc* __restrict__ descs_up, TileDesc* __restrict__ descs_down) {
     __shared__ int first[256];
     __shared__ int tail_key[256];
@@ -522,6 +522,8 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
             if (pos < E) { group = pos; row_begin = offsets[pos]; rows = offsets[pos + 1] - row_begin; srow = -1; }
             else { const int s = pos - E + 1; group = E + s; rows = T; row_begin = 0; srow = s * t_pad; }
         }
+        // a streamed pass covers routed experts [e_lo, e_hi) and, if shared_on, the shared experts
+        if (group < E ? (group < e_lo || group >= e_hi) : !shared_on) rows = 0;
     }
     for (int which = 0; which < 2; ++which) {
         const int tm = which == 0 ? tm_up : tm_down;
@@ -596,9 +598,11 @@ hipError_t ffn_gemm_init() {
 }
 
 hipError_t launch_ffn_plan(const moe_shape& s, const int32_t* offsets, int tm_up, int tm_down, bool tails_last_up,
-                           bool tails_last_down, PlanHeader* plan, TileDesc* descs_up, TileDesc* descs_down, hipStream_t st) {
+                           bool tails_last_down, int e_lo, int e_hi, bool shared_on, PlanHeader* plan,
+                           TileDesc* descs_up, TileDesc* descs_down, hipStream_t st) {
     hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(256), 0, st, offsets, s.T, (s.T + 15) & ~15, s.E, s.num_shared, tm_up, tm_down,
-                       tails_last_up ? 1 : 0, tails_last_down ? 1 : 0, plan, descs_up, descs_down);
+                       tails_last_up ? 1 : 0, tails_last_down ? 1 : 0, e_lo, e_hi, shared_on ? 1 : 0, plan, descs_up,
+                       descs_down);
     return hipGetLastError();
 }
 

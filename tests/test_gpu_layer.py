@@ -182,3 +182,49 @@ def test_layer_full_size_sampled(moe, name, nsample):
     os.makedirs(OUT_DIR, exist_ok=True)
     with open(os.path.join(OUT_DIR, "parity_%s.json" % name), "w") as f:
         json.dump(rep, f)
+
+
+STREAMED = [
+    # name, overrides, experts per group, slots
+    ("C2", dict(T=600, H=256, F=448), 1, 2),                    # one expert at a time, double buffer
+    ("C4", dict(T=640, H=256, F=192), 8, 3),                    # groups of 8, shared experts as the last group
+    ("C5b", dict(T=400, H=128, F=128), 4, 2),                   # most experts empty: they are not fetched
+    ("C5", dict(T=900, H=320, F=128, E=37, top_k=3), 5, 2),     # E not a multiple of the group size
+]
+
+
+@pytest.mark.parametrize("name,over,per_group,num_slots", STREAMED)
+def test_streamed_weights_equal_resident(moe, name, over, per_group, num_slots):
+    """moe_layer_streamed (expert weights in pinned host memory, fetched group by group into
+    staging slots on a side stream) gives the bits of moe_layer, twice in a row, and fetches
+    only experts that received rows."""
+    cfg = scaled_config(name, **over)
+    say("streamed", cfg, per_group, num_slots)
+    gl = P.GpuLayer(moe, make_layer_inputs(cfg, device="cuda"), host_weights=False)
+    ref = gl.run_layer(True)
+    counts = moe.layer_views(gl.shape, gl.ws)["expert_offsets"].cpu().diff().numpy()
+    host = [[w.cpu().pin_memory() for w in ws] for ws in (gl.w1p, gl.w3p, gl.w2p)]
+    expert_bytes = 3 * cfg.H * cfg.F * 2
+    slot_bytes = max(per_group, cfg.num_shared) * expert_bytes
+    slots = torch.empty(num_slots * slot_bytes, dtype=torch.uint8, device="cuda")
+    out = torch.empty_like(ref)
+    moe.set_option("out_fp32", 1)
+    try:
+        for _ in range(2):
+            out.fill_(float("nan"))
+            moe.layer_streamed(gl.shape, gl.x, gl.wg, gl.bias, host[0], host[1], host[2], slots, num_slots, per_group,
+                               out, gl.ws)
+            torch.cuda.synchronize()
+            assert torch.equal(ref, out)
+    finally:
+        moe.set_option("out_fp32", 0)
+    st = moe.stream_stats()
+    live = int((counts > 0).sum()) + cfg.num_shared
+    assert st["bytes_copied"] == live * expert_bytes
+    assert st["experts_skipped"] == int((counts == 0).sum())
+    say(st)
+    # a slot that cannot hold a group is refused before anything runs
+    from paper_2503_09716_amd import MoeError
+    with pytest.raises(MoeError):
+        moe.layer_streamed(gl.shape, gl.x, gl.wg, gl.bias, host[0], host[1], host[2], slots[:2 * expert_bytes - 256], 2,
+                           max(2, per_group), out, gl.ws)
