@@ -53,6 +53,9 @@ def main():
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--option", action="append", default=[], help="library tuning knob key=value")
+    ap.add_argument("--streamed", type=int, default=0, metavar="G",
+                    help="also time moe_layer_streamed (expert weights in pinned host memory, G experts per group, "
+                         "two staging slots) and report it in a 'streamed' object")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="after the timed steps, run one plain device copy of this many MiB (a kernel of known "
                          "HBM traffic for scaling the profiler's FETCH_SIZE / WRITE_SIZE counters)")
@@ -146,6 +149,25 @@ def main():
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
                      "avg_launch_ms": g1_ms, "flops_per_launch": flops_g1},
     }
+    if args.streamed:
+        G = args.streamed
+        host = [[w.cpu().pin_memory() for w in ws_] for ws_ in (w1p, w3p, w2p)]
+        expert_bytes = 3 * cfg.H * cfg.F * 2
+        slots = torch.empty(2 * max(G, cfg.num_shared) * expert_bytes, dtype=torch.uint8, device="cuda")
+        for _ in range(2):
+            moe.layer_streamed(shape, li.x, li.wg, bias, host[0], host[1], host[2], slots, 2, G, out, ws)
+        torch.cuda.synchronize()
+        n = max(3, args.steps // 4)
+        t0 = time.perf_counter()
+        for _ in range(n):
+            moe.layer_streamed(shape, li.x, li.wg, bias, host[0], host[1], host[2], slots, 2, G, out, ws)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / n * 1e3
+        st = moe.stream_stats()
+        result["streamed"] = {"experts_per_group": G, "slots": 2, "ms_per_step": ms, "tokens/s": cfg.T / (ms * 1e-3),
+                              "host_to_device_GB/s": st["bytes_copied"] / (ms * 1e-3) / 1e9,
+                              "bytes_copied_per_step": st["bytes_copied"], "groups": st["groups"],
+                              "experts_skipped": st["experts_skipped"]}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, li)
     print(json.dumps(result))
