@@ -36,6 +36,9 @@ SMALL = [
     ("C4", dict(T=640, H=256, F=192)),                       # 64 experts top-6 + 2 shared
     ("C5", dict(T=900, H=320, F=128)),                       # 160 experts, log-Zipf skew, tiny groups
     ("C5b", dict(T=400, H=128, F=128)),                      # most experts empty
+    ("C1", dict(T=1, H=64, F=64, E=4, top_k=2)),             # one token, smallest widths
+    ("C4", dict(T=96, H=64, F=64, E=254, top_k=32, num_shared=2)),   # E + shared = 256 groups, wide top-k
+    ("C4", dict(T=70, H=128, F=64, E=8, top_k=8, num_shared=8)),     # k = E, 8 shared experts
 ]
 
 

@@ -41,6 +41,8 @@ ROUTE_CASES = [
     ("C5", dict(T=300, H=384)),                   # 2 K-splits, 160 experts padded to 160
     ("C5", dict(T=130, H=192, E=17, top_k=5)),    # 1 K-split, 17 experts padded to 32
     ("C3", dict(T=64, H=128, E=256, top_k=8)),
+    ("C4", dict(T=50, H=64, E=256, top_k=64, num_shared=0)),    # the largest expert count and k the library accepts
+    ("C5", dict(T=1, H=64, E=160, top_k=6)),      # a single token through the matrix-core path
 ]
 
 
