@@ -105,9 +105,9 @@ size_t moe_h_scratch_bytes(const moe_shape* shape);
  *   "x_tiled"         -1|0|1  moe_layer: 1 gathers x once into a block-tiled x_perm that the gate/up GEMM
  *                             loads in 1 KiB pieces, 0 fuses the gather into that GEMM's loads, -1 (default)
  *                             chooses by expert width.  Same results bit for bit.
- *   "tails_last"      -1|0|1  order of a GEMM's tiles: 1 = the short tail tile of every expert after all
- *                             full-height tiles, longest first; 0 = behind its own expert's tiles; -1 (default)
- *                             chooses 1 for launches with few rounds of tiles.  Same results bit for bit.
+ *   "tails_last"      -1|0|1  order of a GEMM's tiles: 1 or -1 (default) = every expert's short tail tile (at most
+ *                             half a tile high) after all other tiles, longest first; 0 = behind its own
+ *                             expert's tiles.  Same results bit for bit.
  *   "probe_k_resident" 0 | 1  timing probe only: the GEMMs re-read their first K tile at every K step
  *                             (operands stay cache resident, RESULTS ARE MEANINGLESS); default 0
  *   "y_fp32"          0 | 1   staged calls: dtype of y_perm / y_shared: 1 (default) fp32, 0 bf16.  bf16 halves the

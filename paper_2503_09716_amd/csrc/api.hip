@@ -306,16 +306,16 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     const int nt_up = (s.F + 127) / 128, nt_down = (s.H + 255) / 256;
     const int tm_up = c->gemm.tile_rows_up ? c->gemm.tile_rows_up : pick_tile_rows(s, nt_up, s.num_shared);
     const int tm_down = c->gemm.tile_rows_down ? c->gemm.tile_rows_down : pick_tile_rows(s, nt_down, s.num_shared ? 1 : 0);
-    // Short tail tiles go last when a launch has only a few rounds of tiles over the 256 CUs
-    // (its end is then a large part of its run time); with many rounds they stay interleaved.
-    const int few_rounds = 14 * 256;
-    const bool tl_up = c->gemm.tails_last >= 0 ? c->gemm.tails_last != 0
-                                               : expected_tiles(s, tm_up, nt_up, s.num_shared) < few_rounds;
-    const bool tl_down = c->gemm.tails_last >= 0 ? c->gemm.tails_last != 0
-                                                 : expected_tiles(s, tm_down, nt_down, s.num_shared ? 1 : 0) < few_rounds;
+    // Short tail tiles go last by default: the other tiles of a launch then all take the same
+    // time, which keeps the CUs that share operand panels in L2 in step (measured: the L2 miss
+    // traffic of the gate/up GEMM doubles when short tiles are mixed in), and the launch ends on
+    // its smallest work items.
+    const bool tl_up = c->gemm.tails_last != 0;
+    const bool tl_down = c->gemm.tails_last != 0;
     {
         StageTimer tm(c, st, MOE_STAGE_PLAN);
-        HIP_TRY(c, launch_ffn_plan(s, offsets, tm_up, tm_down, tl_up, tl_down, ps.e_lo, ps.e_hi, ps.shared_on, plan,
+        HIP_TRY(c, launch_ffn_plan(s, offsets, tm_up, tm_down, tl_up, tl_down, c->gemm.small_tiles != 0, ps.e_lo, ps.e_hi,
+                                   ps.shared_on, plan,
                                    descs_up, descs_down, st));
     }
     GemmArgs a;

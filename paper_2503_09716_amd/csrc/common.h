@@ -101,8 +101,8 @@ hipError_t launch_permute_gather_tiled(const moe_shape& s, const void* x, const 
 
 // the lists cover routed experts [e_lo, e_hi) and, if shared_on, the shared experts
 hipError_t launch_ffn_plan(const moe_shape& s, const int32_t* offsets, int tm_up, int tm_down, bool tails_last_up,
-                           bool tails_last_down, int e_lo, int e_hi, bool shared_on, PlanHeader* plan,
-                           TileDesc* descs_up, TileDesc* descs_down, hipStream_t st);
+                           bool tails_last_down, bool small_tiles, int e_lo, int e_hi, bool shared_on,
+                           PlanHeader* plan, TileDesc* descs_up, TileDesc* descs_down, hipStream_t st);
 hipError_t launch_ffn_gemm(bool gated, const GemmArgs& a, const GemmConfig& cfg, hipStream_t st);
 hipError_t ffn_gemm_init();  // one-time function attributes (dynamic LDS size)
 

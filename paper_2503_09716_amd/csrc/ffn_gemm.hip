@@ -497,15 +497,17 @@ __global__ __launch_bounds__(512, 2) void ffn_gemm_kernel8(const GemmArgs p) {
 // Builds the two m-tile lists (gate/up GEMM with tiles of tm_up rows, down GEMM with tm_down rows)
 // from expert_offsets.  Group order: shared expert 0, routed experts, shared experts 1.. (the down
 // GEMM takes the first two parts only: shared experts are concatenated along K there).
-// A group of n rows gives floor(n/tm) full tiles and at most one short tail tile (the kernel
-// runs a short variant on it).  tails_last = 0: the tail directly follows its group's full
-// tiles, which keeps the load-bound short tiles mixed with the compute-bound full ones (better
-// when a launch has many rounds of tiles).  tails_last = 1: all full tiles come first and the
-// tails follow sorted by falling height, ties in group order, so a launch with few rounds ends
-// on its smallest work items.  n_run_* = number of entries listed in group order.
+// A group of n rows gives floor(n/tm) full tiles and at most one tail tile.  A tail higher than
+// half a tile runs the full-height variant and always stays with its group; a short tail runs
+// a short variant.  tails_last = 0: the short tail, too, directly follows its group's tiles,
+// which keeps the load-bound short tiles mixed with the compute-bound full ones (better when
+// a launch has many rounds of tiles).  tails_last = 1: the short tails follow all other tiles,
+// sorted by falling height, ties in group order, so a launch with few rounds ends on its
+// smallest work items and its other tiles all take the same time (CUs that share operand
+// panels in L2 stay in step).  n_run_* = number of entries listed in group order.
 __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict__ offsets, int T, int t_pad, int E, int Ns,
                                                        int tm_up, int tm_down, int tails_last_up, int tails_last_down,
-                                                       int e_lo, int e_hi, int shared_on, PlanHeader* __restrict__ plan,
+                                                       int small_tiles, int e_lo, int e_hi, int shared_on, PlanHeader* __restrict__ plan,
                                                        TileDesc* __restrict__ descs_up, TileDesc* __restrict__ descs_down) {
     __shared__ int first[256];
     __shared__ int tail_key[256];
@@ -534,10 +536,14 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
         const int nfull = mine ? rows / tm : 0;
         const int tail = mine ? rows - nfull * tm : 0;
         const int blocks = (tail + 31) >> 5;   // 32-row blocks of the tail tile, 0 = none
-        const int nrun = tails_last ? nfull : nfull + (blocks > 0);   // tiles listed in group order
+        // A tail higher than half a tile runs the full-height variant and takes as long as a full
+        // tile, so it stays with its group (keeps the group's W panels shared and the CUs in
+        // step); only a short tail is moved to the end of the list.
+        const bool moved = tails_last && blocks > 0 && small_tiles && blocks * 64 <= tm;
+        const int nrun = nfull + (blocks > 0 && !moved);   // tiles listed in group order
         __syncthreads();
         first[tid] = nrun;
-        tail_key[tid] = blocks;
+        tail_key[tid] = moved ? blocks : 0;
         __syncthreads();
         if (tid == 0) {
             int run = 0, tails = 0;
@@ -548,7 +554,7 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
                 tails += tail_key[i] > 0;
             }
             n_run_s = run;
-            const int total = tails_last ? run + tails : run;
+            const int total = run + tails;
             if (which == 0) { plan->n_gate_up = total; plan->n_run_up = run; }
             else { plan->n_down = total; plan->n_run_down = run; }
         }
@@ -563,7 +569,7 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
                 d.nrows = min(tm, rows - i * tm);
                 descs[base + i] = d;
             }
-            if (tails_last && blocks > 0) {
+            if (moved) {
                 int rank = 0;   // tails that come before this one
                 for (int i = 0; i <= last; ++i) {
                     const int b = tail_key[i];
@@ -598,10 +604,10 @@ hipError_t ffn_gemm_init() {
 }
 
 hipError_t launch_ffn_plan(const moe_shape& s, const int32_t* offsets, int tm_up, int tm_down, bool tails_last_up,
-                           bool tails_last_down, int e_lo, int e_hi, bool shared_on, PlanHeader* plan,
-                           TileDesc* descs_up, TileDesc* descs_down, hipStream_t st) {
+                           bool tails_last_down, bool small_tiles, int e_lo, int e_hi, bool shared_on,
+                           PlanHeader* plan, TileDesc* descs_up, TileDesc* descs_down, hipStream_t st) {
     hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(256), 0, st, offsets, s.T, (s.T + 15) & ~15, s.E, s.num_shared, tm_up, tm_down,
-                       tails_last_up ? 1 : 0, tails_last_down ? 1 : 0, e_lo, e_hi, shared_on ? 1 : 0, plan, descs_up,
+                       tails_last_up ? 1 : 0, tails_last_down ? 1 : 0, small_tiles ? 1 : 0, e_lo, e_hi, shared_on ? 1 : 0, plan, descs_up,
                        descs_down);
     return hipGetLastError();
 }
