@@ -108,6 +108,10 @@ size_t moe_h_scratch_bytes(const moe_shape* shape);
  *   "tails_last"      -1|0|1  order of a GEMM's tiles: 1 or -1 (default) = every expert's short tail tile (at most
  *                             half a tile high) after all other tiles, longest first; 0 = behind its own
  *                             expert's tiles.  Same results bit for bit.
+ *   "down_tail_splits" 0 | 1  1 (default): with at most 32 experts the down projection cuts the contraction range of
+ *                             every short tail tile into 2 or 4 pieces run by different CUs and adds the fp32
+ *                             partial sums afterwards in fixed order; 0: one piece.  Changes the summation
+ *                             order of those rows only (not bit-identical between 0 and 1).
  *   "probe_k_resident" 0 | 1  timing probe only: the GEMMs re-read their first K tile at every K step
  *                             (operands stay cache resident, RESULTS ARE MEANINGLESS); default 0
  *   "y_fp32"          0 | 1   staged calls: dtype of y_perm / y_shared: 1 (default) fp32, 0 bf16.  bf16 halves the

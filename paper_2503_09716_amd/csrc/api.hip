@@ -27,7 +27,7 @@ struct ProfRec {
 struct moe_ctx {
     int device = 0;
     char err[512] = {0};
-    GemmConfig gemm{1, 4, 8, 1, 1, 0, 0, -1, -1, 0};
+    GemmConfig gemm{1, 4, 8, 1, 1, 0, 0, -1, -1, 1, 0};
     bool y_fp32 = true;    // dtype of y_perm / y_shared in the staged calls
     int layer_y = -1;      // moe_layer's y_perm: 1 fp32, 0 bf16, -1 choose (its y_shared is always fp32)
     bool out_fp32 = false; // dtype of the layer output
@@ -108,10 +108,21 @@ RouteGemm route_gemm_config(const moe_shape& s) {
     return r;
 }
 
+// K pieces per short tail tile of the down GEMM.  A short tail of the down projection streams a
+// whole 256-row panel of W2 for a few rows of work, and few of them run at a time at the end of
+// the launch, each limited by what one CU can load; cutting K spreads that over more CUs.  The
+// partial sums need E * pieces * 128 fp32 rows of workspace, so this is for few experts only.
+int down_tail_splits(const moe_shape& s) {
+    if (s.E > 32) return 1;
+    for (int sp : {4, 2})
+        if (s.F % (32 * sp) == 0 && s.F / (32 * sp) >= 8) return sp;
+    return 1;
+}
+
 // Workspace layout: fixed order, every region 256-byte aligned.
 struct Layout {
     size_t topk_idx, topk_w, offsets, perm, inv_perm, row_token, chunk_counts, plan, descs_up, descs_down,
-        rt_plan, rt_table, rt_descs, rt_wg, rt_logits, x_tiled, h, y_perm, y_shared, total;
+        split_tails, split_partial, rt_plan, rt_table, rt_descs, rt_wg, rt_logits, x_tiled, h, y_perm, y_shared, total;
 };
 
 Layout make_layout(const moe_shape& s) {
@@ -128,7 +139,10 @@ Layout make_layout(const moe_shape& s) {
     L.chunk_counts = take((size_t)permute_chunks(s) * s.E * 4);
     L.plan = take(sizeof(PlanHeader));
     L.descs_up = take((size_t)max_mtiles(s, 128) * sizeof(TileDesc));
-    L.descs_down = take((size_t)max_mtiles(s, 128) * sizeof(TileDesc));
+    const int dsp = down_tail_splits(s);
+    L.descs_down = take(((size_t)max_mtiles(s, 128) + (size_t)s.E * (dsp - 1)) * sizeof(TileDesc));
+    L.split_tails = take((size_t)s.E * sizeof(SplitTail));
+    L.split_partial = take(dsp > 1 ? (size_t)s.E * dsp * SPLIT_TAIL_ROWS * s.H * 4 : 0);
     // router GEMM (E > 16): plan, W pointer per K-split, tile list, packed gate matrix, partial logits
     const RouteGemm rg = route_gemm_config(s);
     L.rt_plan = take(rg.splits ? sizeof(PlanHeader) : 0);
@@ -256,6 +270,8 @@ moe_status run_route(moe_ctx* c, const moe_shape& s, const void* x, const void* 
     a.split_rows = s.T;
     a.a_tiled = 0;
     a.t_pad = (s.T + 15) & ~15;
+    a.kt_a = 0;
+    a.tail_splits = 1;
     GemmConfig cfg = c->gemm;
     cfg.waves = 4;
     cfg.wave_rows = 2;
@@ -312,10 +328,12 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     // its smallest work items.
     const bool tl_up = c->gemm.tails_last != 0;
     const bool tl_down = c->gemm.tails_last != 0;
+    const int dsp = (tl_down && c->gemm.small_tiles && c->gemm.down_tail_splits != 0) ? down_tail_splits(s) : 1;
+    SplitTail* split_tails = (SplitTail*)(ws + L.split_tails);
     {
         StageTimer tm(c, st, MOE_STAGE_PLAN);
         HIP_TRY(c, launch_ffn_plan(s, offsets, tm_up, tm_down, tl_up, tl_down, c->gemm.small_tiles != 0, ps.e_lo, ps.e_hi,
-                                   ps.shared_on, plan,
+                                   ps.shared_on, dsp, split_tails, plan,
                                    descs_up, descs_down, st));
     }
     GemmArgs a;
@@ -344,6 +362,8 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     a.N = s.F;
     a.lda_bytes = s.H * 2;
     a.kt_w = s.H / 32;
+    a.kt_a = s.H / 32;
+    a.tail_splits = 1;
     a.nseg_shared = 1;
     a.n_tiles = nt_up;
     {
@@ -352,7 +372,7 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     }
     // GEMM 2: h [rows, F] x W2p [H, F] -> y [rows, H]
     a.descs = descs_down;
-    a.max_mtiles = ps.mtiles_down > 0 ? ps.mtiles_down : (int)max_mtiles(s, tm_down);
+    a.max_mtiles = (ps.mtiles_down > 0 ? ps.mtiles_down : (int)max_mtiles(s, tm_down)) + s.E * (dsp - 1);
     a.a_routed = (const char*)h;
     a.a_shared = (const char*)h + Rpad * s.F * 2;
     a.row_token = nullptr;
@@ -365,12 +385,17 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     a.N = s.H;
     a.lda_bytes = s.F * 2;
     a.kt_w = s.F / 32;
+    a.kt_a = s.F / 32;
+    a.tail_splits = dsp;
+    a.out_partial = ws + L.split_partial;
     a.nseg_shared = s.num_shared > 0 ? s.num_shared : 1;
     a.out_fp32 = (y_fp32 ? 1 : 0) | (shared_fp32 ? 2 : 0);
     a.n_tiles = nt_down;
     {
         StageTimer tm(c, st, MOE_STAGE_FFN_DOWN);
         HIP_TRY(c, launch_ffn_gemm(false, a, c->gemm, st));
+        if (dsp > 1)
+            HIP_TRY(c, launch_split_tail_reduce(s, plan, split_tails, (const float*)(ws + L.split_partial), dsp, y_perm, y_fp32, st));
     }
     return MOE_OK;
 }
@@ -498,6 +523,7 @@ moe_status moe_set_option(moe_ctx* c, const char* key, int32_t v) {
     if (!strcmp(key, "gemm_tile_rows_up") && (v == 0 || v == 128 || v == 256)) { c->gemm.tile_rows_up = v; return MOE_OK; }
     if (!strcmp(key, "gemm_tile_rows_down") && (v == 0 || v == 128 || v == 256)) { c->gemm.tile_rows_down = v; return MOE_OK; }
     if (!strcmp(key, "x_tiled") && v >= -1 && v <= 1) { c->gemm.x_tiled = v; return MOE_OK; }
+    if (!strcmp(key, "down_tail_splits") && (v == 0 || v == 1)) { c->gemm.down_tail_splits = v; return MOE_OK; }
     if (!strcmp(key, "tails_last") && v >= -1 && v <= 1) { c->gemm.tails_last = v; return MOE_OK; }
     if (!strcmp(key, "probe_k_resident") && (v == 0 || v == 1)) { c->gemm.probe_k_resident = v; return MOE_OK; }
     if (!strcmp(key, "y_fp32") && (v == 0 || v == 1)) { c->y_fp32 = v != 0; return MOE_OK; }

@@ -19,6 +19,8 @@ __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_
 //   routed group : group = expert id, row0 = permuted row, srow = -1
 //   router GEMM  : group = K-split index s, row0 = first token, srow = -1 - s
 //   shared group : group = E + s,     row0 = first token,  srow = s * t_pad (row offset inside the shared region of h)
+//   K-split piece of a short tail of the down GEMM: group = expert id, row0 = permuted row,
+//                  srow = -1 - (q * splits + s) for piece s of the q-th split tail
 struct TileDesc {
     int32_t group;
     int32_t row0;
@@ -31,7 +33,15 @@ struct PlanHeader {
     int32_t n_down;     // m-tiles of GEMM 2 (routed + shared expert 0; shared experts are K-concatenated)
     int32_t n_run_up;   // the first n_run_* entries of each list are in group order; short tail tiles moved
     int32_t n_run_down; // to the end of the list (if any) follow them
+    int32_t n_split_tails;  // down GEMM: short tails whose K range is cut into pieces (0 if that is off)
+    int32_t pad[3];
 };
+
+// Rows of y_perm that the K-split pieces of one short tail add up to.
+struct SplitTail {
+    int32_t row0, nrows;
+};
+constexpr int SPLIT_TAIL_ROWS = 128;   // a split tail is at most half a 256-row tile high
 
 struct GemmArgs {
     const char* a_routed;      // GEMM1: x_perm, or x when row_token != nullptr; GEMM2: h
@@ -56,6 +66,9 @@ struct GemmArgs {
     int32_t lda_bytes;         // row stride of a row-major A operand
     int32_t kt_w;              // 1 KiB blocks per 16-row group of the packed W (its full K / 32)
     int32_t split_rows;        // router GEMM: output rows per K-split (partial s is written at rows s*split_rows + ...)
+    int32_t kt_a;              // 1 KiB blocks per 16-row group of a tiled A operand (its full K / 32)
+    int32_t tail_splits;       // down GEMM: K pieces per short tail (entries past n_run; 1 = not split)
+    char* out_partial;         // down GEMM: fp32 partial results of split tails, SPLIT_TAIL_ROWS rows per piece
     int32_t a_tiled;           // A operand is in 16 x 32 blocks (else row-major): bit 0 routed tiles, bit 1 shared tiles
     int32_t t_pad;             // T rounded up to 16: rows of one shared expert's block of h
 };
@@ -70,6 +83,7 @@ struct GemmConfig {
     int tile_rows_down;    // same for the down GEMM
     int x_tiled;           // moe_layer: 1 = gather x into a tiled x_perm first, 0 = gather inside GEMM 1, -1 = choose
     int tails_last;        // order of the m-tile lists: 1 = short tail tiles after all full tiles, 0 = in group order, -1 = choose
+    int down_tail_splits;  // 1: the down GEMM cuts the K range of short tail tiles into pieces (few experts only); 0: off
     int probe_k_resident;  // timing probe: every K step re-reads the first tile (results are meaningless)
 };
 
@@ -102,7 +116,11 @@ hipError_t launch_permute_gather_tiled(const moe_shape& s, const void* x, const 
 // the lists cover routed experts [e_lo, e_hi) and, if shared_on, the shared experts
 hipError_t launch_ffn_plan(const moe_shape& s, const int32_t* offsets, int tm_up, int tm_down, bool tails_last_up,
                            bool tails_last_down, bool small_tiles, int e_lo, int e_hi, bool shared_on,
-                           PlanHeader* plan, TileDesc* descs_up, TileDesc* descs_down, hipStream_t st);
+                           int down_tail_splits, SplitTail* split_tails, PlanHeader* plan, TileDesc* descs_up,
+                           TileDesc* descs_down, hipStream_t st);
+// y_perm rows of the split tails = sum over pieces of the fp32 partials, in y_perm's dtype
+hipError_t launch_split_tail_reduce(const moe_shape& s, const PlanHeader* plan, const SplitTail* tails, const float* partial,
+                                    int splits, void* y_perm, bool y_fp32, hipStream_t st);
 hipError_t launch_ffn_gemm(bool gated, const GemmArgs& a, const GemmConfig& cfg, hipStream_t st);
 hipError_t ffn_gemm_init();  // one-time function attributes (dynamic LDS size)
 

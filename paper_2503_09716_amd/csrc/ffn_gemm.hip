@@ -163,9 +163,16 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
     const int K = p.K, N = p.N;
     const int n0 = n_tile * BN;
     const bool shared = d.srow >= 0;
-    const int split = shared ? 0 : -1 - d.srow;   // K-split index (router GEMM only; 0 elsewhere)
+    // K-split.  Router GEMM: srow = -1 - s, the operands of piece s start s*K further along and
+    // its partial output goes to rows s*split_rows + ...  Down GEMM with tail_splits > 1: a short
+    // tail is cut into tail_splits pieces along K; srow = -2 - u, u counting the pieces of all
+    // split tails; piece u covers K range (u % tail_splits) * K/tail_splits .. and writes fp32
+    // partials to rows u * SPLIT_TAIL_ROWS of out_partial.
+    const bool tail_split = !GATED && p.tail_splits > 1 && d.srow <= -2;
+    const int piece = tail_split ? -2 - d.srow : (shared ? 0 : -1 - d.srow);
+    const int split = tail_split ? piece % p.tail_splits : piece;
     const int nseg = (!GATED && shared) ? p.nseg_shared : 1;
-    const int KT = K / BK;   // sub-tiles per segment (>= 2)
+    const int KT = (tail_split ? K / p.tail_splits : K) / BK;   // sub-tiles per segment (>= 2)
     // K step in bytes: one 1 KiB block for tiled operands, 64 bytes along a row for row-major x
     const int kstep_w = p.k_step_on ? 1024 : 0;
     // A operand layout (bit 0: routed tiles, bit 1: shared tiles): h is tiled; x is row-major
@@ -200,7 +207,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
             } else {
                 // h: tiled; the piece this lane needs sits at slot piece ^ ((row%16)/4) of its row
                 const int rr = grow & 15;
-                loff[i] = (uint32_t)(grow >> 4) * (uint32_t)(KT * 1024) + (uint32_t)(rr * 64 + ((lpiece ^ (rr >> 2)) << 4));
+                loff[i] = (uint32_t)(grow >> 4) * (uint32_t)(p.kt_a * 1024) + (uint32_t)(rr * 64 + ((lpiece ^ (rr >> 2)) << 4));
             }
         } else {
             // W: tiled and row-permuted by the pack step, so LDS rows (q-NQX)*16 .. +15 of the W region
@@ -301,8 +308,11 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
     // every other tile has one segment.  The pipeline drains and restarts between segments.
     for (int seg = 0; seg < nseg; ++seg) {
         // the descriptors span 4 GiB - 1; bounds are kept by the row clamps above
-        rs_x = uniform_rsrc(a_base + (size_t)seg * a_seg_stride + (size_t)split * (size_t)K * 2);
-        rs_w = uniform_rsrc(p.w_a[d.group + seg]);
+        // a K piece starts `split` pieces along: K*2 bytes per piece in a row-major row, KT blocks of
+        // 1 KiB in a tiled operand (the packed W is always tiled)
+        const size_t piece_shift = (size_t)split * (size_t)KT * 1024;
+        rs_x = uniform_rsrc(a_base + (size_t)seg * a_seg_stride + (tail_split ? piece_shift : (size_t)split * (size_t)K * 2));
+        rs_w = uniform_rsrc((const char*)p.w_a[d.group + seg] + (tail_split ? piece_shift : 0));
         if (GATED) rs_u = uniform_rsrc(p.w_b[d.group]);
         koff_x = 0;
         koff_w = 0;
@@ -354,8 +364,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
     // Accumulator block (j, i) is 16 x 16; a lane holds 4 registers: the block's MFMA-row-operand
     // index 4*(lane/16) + r and column-operand index lane%16.
     mfma_drain();
-    char* out = shared ? p.out_shared : p.out_routed;
-    const int orow_base = (shared ? (GATED ? d.srow : 0) : split * p.split_rows) + d.row0;
+    char* out = shared ? p.out_shared : (tail_split ? p.out_partial : p.out_routed);
+    const int orow_base = tail_split ? piece * SPLIT_TAIL_ROWS
+                                     : (shared ? (GATED ? d.srow : 0) : split * p.split_rows) + d.row0;
     if (GATED) {
         // W is the row operand: the lane owns output row (X row) lane%16 of block i and the 4
         // consecutive columns 4*(lane/16) .. +3 of gate block j; the up value of the same
@@ -410,7 +421,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
                 __builtin_amdgcn_sched_barrier(0);   // one block row at a time
             }
         };
-        if ((shared ? p.out_fp32 >> 1 : p.out_fp32) & 1) store_tile(T_{});
+        if (tail_split || ((shared ? p.out_fp32 >> 1 : p.out_fp32) & 1)) store_tile(T_{});
         else store_tile(F_{});
     }
 }
@@ -507,7 +518,8 @@ __global__ __launch_bounds__(512, 2) void ffn_gemm_kernel8(const GemmArgs p) {
 // panels in L2 stay in step).  n_run_* = number of entries listed in group order.
 __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict__ offsets, int T, int t_pad, int E, int Ns,
                                                        int tm_up, int tm_down, int tails_last_up, int tails_last_down,
-                                                       int small_tiles, int e_lo, int e_hi, int shared_on, PlanHeader* __restrict__ plan,
+                                                       int small_tiles, int e_lo, int e_hi, int shared_on, int down_splits,
+                                                       SplitTail* __restrict__ split_tails, PlanHeader* __restrict__ plan,
                                                        TileDesc* __restrict__ descs_up, TileDesc* __restrict__ descs_down) {
     __shared__ int first[256];
     __shared__ int tail_key[256];
@@ -554,9 +566,10 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
                 tails += tail_key[i] > 0;
             }
             n_run_s = run;
-            const int total = run + tails;
+            const int per_tail = which == 1 ? down_splits : 1;   // list entries per moved tail
+            const int total = run + tails * per_tail;
             if (which == 0) { plan->n_gate_up = total; plan->n_run_up = run; }
-            else { plan->n_down = total; plan->n_run_down = run; }
+            else { plan->n_down = total; plan->n_run_down = run; plan->n_split_tails = down_splits > 1 ? tails : 0; }
         }
         __syncthreads();
         if (mine) {
@@ -577,13 +590,58 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
                 }
                 d.row0 = row_begin + nfull * tm;
                 d.nrows = tail;
-                descs[n_run_s + rank] = d;
+                if (which == 1 && down_splits > 1) {
+                    // one entry per K piece; the pieces' partial sums are added up after the launch
+                    for (int sp = 0; sp < down_splits; ++sp) {
+                        d.srow = -2 - (rank * down_splits + sp);
+                        descs[n_run_s + rank * down_splits + sp] = d;
+                    }
+                    split_tails[rank].row0 = d.row0;
+                    split_tails[rank].nrows = tail;
+                } else {
+                    descs[n_run_s + rank] = d;
+                }
             }
         }
     }
 }
 
+// y_perm[row0 + r, :] of split tail q = sum over its K pieces of the fp32 partials, added in
+// piece order (one thread per 4 columns, one workgroup per row): deterministic.
+__global__ __launch_bounds__(256) void split_tail_reduce_kernel(const PlanHeader* __restrict__ plan,
+                                                                const SplitTail* __restrict__ tails,
+                                                                const float* __restrict__ partial, int splits, int H,
+                                                                char* __restrict__ y, int y_fp32) {
+    const int q = blockIdx.x / SPLIT_TAIL_ROWS, r = blockIdx.x % SPLIT_TAIL_ROWS;
+    if (q >= plan->n_split_tails) return;
+    const SplitTail t = tails[q];
+    if (r >= t.nrows) return;
+    for (int c = threadIdx.x * 4; c < H; c += 256 * 4) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int sp = 0; sp < splits; ++sp) {
+            const f32x4 v = *reinterpret_cast<const f32x4*>(partial + ((size_t)(q * splits + sp) * SPLIT_TAIL_ROWS + r) * H + c);
+            acc += v;
+        }
+        const size_t at = (size_t)(t.row0 + r) * H + c;
+        if (y_fp32) {
+            *reinterpret_cast<f32x4*>(y + at * 4) = acc;
+        } else {
+            bf16x4 o;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[i] = (__bf16)acc[i];
+            *reinterpret_cast<bf16x4*>(y + at * 2) = o;
+        }
+    }
+}
+
 }  // namespace
+
+hipError_t launch_split_tail_reduce(const moe_shape& s, const PlanHeader* plan, const SplitTail* tails, const float* partial,
+                                    int splits, void* y_perm, bool y_fp32, hipStream_t st) {
+    hipLaunchKernelGGL(split_tail_reduce_kernel, dim3((unsigned)(s.E * SPLIT_TAIL_ROWS)), dim3(256), 0, st, plan, tails, partial,
+                       splits, s.H, (char*)y_perm, y_fp32 ? 1 : 0);
+    return hipGetLastError();
+}
 
 hipError_t ffn_gemm_init() {
     hipError_t e;
@@ -605,10 +663,11 @@ hipError_t ffn_gemm_init() {
 
 hipError_t launch_ffn_plan(const moe_shape& s, const int32_t* offsets, int tm_up, int tm_down, bool tails_last_up,
                            bool tails_last_down, bool small_tiles, int e_lo, int e_hi, bool shared_on,
-                           PlanHeader* plan, TileDesc* descs_up, TileDesc* descs_down, hipStream_t st) {
+                           int down_tail_splits, SplitTail* split_tails, PlanHeader* plan, TileDesc* descs_up,
+                           TileDesc* descs_down, hipStream_t st) {
     hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(256), 0, st, offsets, s.T, (s.T + 15) & ~15, s.E, s.num_shared, tm_up, tm_down,
-                       tails_last_up ? 1 : 0, tails_last_down ? 1 : 0, small_tiles ? 1 : 0, e_lo, e_hi, shared_on ? 1 : 0, plan, descs_up,
-                       descs_down);
+                       tails_last_up ? 1 : 0, tails_last_down ? 1 : 0, small_tiles ? 1 : 0, e_lo, e_hi, shared_on ? 1 : 0,
+                       tails_last_down ? down_tail_splits : 1, split_tails, plan, descs_up, descs_down);
     return hipGetLastError();
 }
 

@@ -206,6 +206,7 @@ __global__ __launch_bounds__(256) void route_plan_kernel(int T, int tm, int spli
         plan->n_down = per * splits;
         plan->n_run_up = 0;
         plan->n_run_down = per * splits;
+        plan->n_split_tails = 0;
     }
 }
 
