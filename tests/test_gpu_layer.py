@@ -239,3 +239,34 @@ def test_streamed_weights_equal_resident(moe, name, over, per_group, num_slots):
     with pytest.raises(MoeError):
         moe.layer_streamed(gl.shape, gl.x, gl.wg, gl.bias, host[0], host[1], host[2], slots[:2 * expert_bytes - 256], 2,
                            max(2, per_group), out, gl.ws)
+
+
+def test_layer_in_a_hip_graph(moe):
+    """moe_layer enqueues kernels only (no memsets, no host synchronisation once its pointer
+    table is uploaded), so it can be captured; every replay, with eager work and
+    synchronisations in between, gives the eager bits."""
+    cfg = scaled_config("C4", T=700, H=256, F=192)
+    gl = P.GpuLayer(moe, make_layer_inputs(cfg, device="cuda"), host_weights=False)
+    ref = gl.run_layer().clone()           # also uploads the weight pointer table
+    out = torch.empty_like(ref)
+
+    def step():
+        moe.layer(gl.shape, gl.x, gl.wg, gl.bias, gl.w1p, gl.w3p, gl.w2p, out, gl.ws, tables=gl.tables)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    torch.cuda.synchronize()
+    for _ in range(4):
+        out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref)
+        eager = gl.run_layer()             # the library's own eager work between replays
+        assert torch.equal(eager, ref)
