@@ -222,6 +222,20 @@ moe_status moe_layer_streamed(moe_ctx* ctx, const moe_shape* shape, const void* 
  * experts skipped because they had no rows.  Any out-pointer may be NULL. */
 moe_status moe_stream_stats(const moe_ctx* ctx, uint64_t* bytes_copied, int32_t* groups, int32_t* experts_skipped);
 
+/* Run-time estimate of moe_layer_streamed's expert phase, in milliseconds (host arithmetic only;
+ * Sec. 4.4: the jobs of an offloaded layer form a DAG of copy and compute nodes, and the
+ * earliest finishing time of each node follows in topological order from
+ * finish[v] = cost[v] + max over predecessors finish[u]; the exit node's value is the estimate).
+ * Nodes: copy(g) and compute(g) for every group g that moe_layer_streamed would form from
+ * rows_per_expert (empty experts skipped, shared experts last).  Edges: copy(g) -> compute(g);
+ * copy(g-1) -> copy(g) (one copy stream); compute(g-1) -> compute(g) (one compute stream);
+ * compute(g-num_slots) -> copy(g) (the slot must be free).
+ * cost(copy g) = bytes of the group's experts / link_gbs; cost(compute g) = 6 * rows * H * F /
+ * ffn_tflops, both rates measured by the caller (e.g. bench.py --streamed, the sweep script).
+ *   rows_per_expert [E] host.  Returns a negative value for invalid arguments. */
+double moe_estimate_streamed_ms(const moe_shape* shape, const int32_t* rows_per_expert, int32_t experts_per_group,
+                                int32_t num_slots, double link_gbs, double ffn_tflops);
+
 /* Device pointers into a workspace last used by moe_layer with this shape, for inspection:
  * topk_idx [T,k] int32, topk_w [T,k] fp32, expert_offsets [E+1] int32, inv_perm [T*k] int32.
  * Any out-pointer may be NULL. */

@@ -20,7 +20,7 @@ STAGES = ["route", "permute_index", "permute_gather", "plan", "ffn_gate_up", "ff
 EXPORTS = [
     "moe_create", "moe_destroy", "moe_last_error", "moe_workspace_bytes", "moe_h_scratch_bytes", "moe_set_option", "moe_pack_weight",
     "moe_route", "moe_permute", "moe_grouped_ffn", "moe_combine", "moe_layer", "moe_layer_views",
-    "moe_layer_streamed", "moe_stream_stats",
+    "moe_layer_streamed", "moe_stream_stats", "moe_estimate_streamed_ms",
     "moe_profile_enable", "moe_profile_read",
 ]
 
@@ -74,8 +74,11 @@ def load_library():
                                     C.POINTER(C.c_void_p)]
     lib.moe_profile_enable.argtypes = [C.c_void_p, C.c_int32]
     lib.moe_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
+    lib.moe_estimate_streamed_ms.argtypes = [sp, C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.c_double, C.c_double]
+    lib.moe_estimate_streamed_ms.restype = C.c_double
     for name in EXPORTS:
-        if name not in ("moe_destroy", "moe_last_error", "moe_workspace_bytes", "moe_h_scratch_bytes"):
+        if name not in ("moe_destroy", "moe_last_error", "moe_workspace_bytes", "moe_h_scratch_bytes",
+                        "moe_estimate_streamed_ms"):
             getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -96,6 +99,14 @@ def workspace_bytes(shape: MoeShape) -> int:
 
 def h_scratch_bytes(shape: MoeShape) -> int:
     return int(load_library().moe_h_scratch_bytes(C.byref(shape)))
+
+
+def estimate_streamed_ms(shape: MoeShape, rows_per_expert, experts_per_group: int, num_slots: int, link_gbs: float,
+                         ffn_tflops: float) -> float:
+    """Critical-path estimate of the expert phase of Moe.layer_streamed (host arithmetic)."""
+    rows = (C.c_int32 * shape.E)(*[int(r) for r in rows_per_expert])
+    return float(load_library().moe_estimate_streamed_ms(C.byref(shape), rows, experts_per_group, num_slots,
+                                                         link_gbs, ffn_tflops))
 
 
 def _ptr(t: Optional[torch.Tensor]):

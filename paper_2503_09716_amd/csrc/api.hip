@@ -705,6 +705,46 @@ moe_status moe_layer_streamed(moe_ctx* c, const moe_shape* s, const void* x, con
     return MOE_OK;
 }
 
+double moe_estimate_streamed_ms(const moe_shape* s, const int32_t* rows, int32_t per_group, int32_t num_slots,
+                                double link_gbs, double ffn_tflops) {
+    moe_status st;
+    if (shape_problem(s, &st) || !rows || per_group < 1 || num_slots < 2 || num_slots > MAX_SLOTS || !(link_gbs > 0) ||
+        !(ffn_tflops > 0))
+        return -1.0;
+    const double expert_ms = 3.0 * s->H * s->F * 2 / (link_gbs * 1e9) * 1e3;
+    const double row_ms = 6.0 * s->H * s->F / (ffn_tflops * 1e12) * 1e3;
+    // job costs per group, formed exactly as moe_layer_streamed forms them
+    std::vector<double> copy_ms, comp_ms;
+    for (int e = 0; e < s->E;) {
+        while (e < s->E && rows[e] <= 0) ++e;
+        if (e >= s->E) break;
+        int n = 0;
+        double r = 0;
+        while (e < s->E && n < per_group) {
+            if (rows[e] > 0) { ++n; r += rows[e]; }
+            ++e;
+        }
+        copy_ms.push_back(n * expert_ms);
+        comp_ms.push_back(r * row_ms);
+    }
+    if (s->num_shared > 0) {
+        copy_ms.push_back(s->num_shared * expert_ms);
+        comp_ms.push_back((double)s->num_shared * s->T * row_ms);
+    }
+    // longest path: nodes in topological order copy(0), compute(0), copy(1), compute(1), ...
+    const size_t G = copy_ms.size();
+    std::vector<double> f_copy(G, 0.0), f_comp(G, 0.0);
+    for (size_t g = 0; g < G; ++g) {
+        double ready = g > 0 ? f_copy[g - 1] : 0.0;
+        if (g >= (size_t)num_slots && f_comp[g - num_slots] > ready) ready = f_comp[g - num_slots];
+        f_copy[g] = ready + copy_ms[g];
+        double start = f_copy[g];
+        if (g > 0 && f_comp[g - 1] > start) start = f_comp[g - 1];
+        f_comp[g] = start + comp_ms[g];
+    }
+    return G ? f_comp[G - 1] : 0.0;
+}
+
 moe_status moe_stream_stats(const moe_ctx* c, uint64_t* bytes, int32_t* groups, int32_t* skipped) {
     if (!c) return MOE_E_ARG;
     if (bytes) *bytes = c->stream_bytes;
