@@ -164,7 +164,10 @@ def main():
         torch.cuda.synchronize()
         ms = (time.perf_counter() - t0) / n * 1e3
         st = moe.stream_stats()
+        from paper_2503_09716_amd import estimate_streamed_ms
+        est = estimate_streamed_ms(shape, cnt.tolist(), G, 2, 56.0, ffn_tflops)   # 56 GB/s: this pool's pinned host-to-device rate
         result["streamed"] = {"experts_per_group": G, "slots": 2, "ms_per_step": ms, "tokens/s": cfg.T / (ms * 1e-3),
+                              "critical_path_estimate_ms_expert_phase": est,
                               "host_to_device_GB/s": st["bytes_copied"] / (ms * 1e-3) / 1e9,
                               "bytes_copied_per_step": st["bytes_copied"], "groups": st["groups"],
                               "experts_skipped": st["experts_skipped"]}
