@@ -210,7 +210,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
                 loff[i] = (uint32_t)(grow >> 4) * (uint32_t)(p.kt_a * 1024) + (uint32_t)(rr * 64 + ((lpiece ^ (rr >> 2)) << 4));
             }
         } else {
-            // W: tiled and row-permuted by the pack step, so LDS rows (q-NQX)*16 .. +15 of the W region
+            // W: tiled by the pack step, so LDS rows (q-NQX)*16 .. +15 of the W region
             // are one 1 KiB block: group index n0/16 + (q-NQX), in lane order.
             const int qw = q - NQX;
             int grp = (n0 >> 4) + (GATED ? (qw & 7) : qw);
