@@ -56,6 +56,9 @@ def main():
     ap.add_argument("--streamed", type=int, default=0, metavar="G",
                     help="also time moe_layer_streamed (expert weights in pinned host memory, G experts per group, "
                          "two staging slots) and report it in a 'streamed' object")
+    ap.add_argument("--blas-reference", action="store_true",
+                    help="context only: time the vendor BLAS (torch.bmm, bf16) on the two dense batched GEMMs that the "
+                         "grouped FFN would be with exactly T*k/E rows per expert, on data of the same distribution")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="after the timed steps, run one plain device copy of this many MiB (a kernel of known "
                          "HBM traffic for scaling the profiler's FETCH_SIZE / WRITE_SIZE counters)")
@@ -171,6 +174,27 @@ def main():
                               "host_to_device_GB/s": st["bytes_copied"] / (ms * 1e-3) / 1e9,
                               "bytes_copied_per_step": st["bytes_copied"], "groups": st["groups"],
                               "experts_skipped": st["experts_skipped"]}
+    if args.blas_reference:
+        from workloads import normal_bf16
+        rows = max(1, R // cfg.E)
+        a1 = normal_bf16(cfg.seed, 101, (cfg.E, rows, cfg.H), 1.0, "cuda")
+        b1 = normal_bf16(cfg.seed, 102, (cfg.E, cfg.H, 2 * cfg.F), 0.02, "cuda")
+        a2 = normal_bf16(cfg.seed, 103, (cfg.E, rows, cfg.F), 1.0, "cuda")
+        b2 = normal_bf16(cfg.seed, 104, (cfg.E, cfg.F, cfg.H), 0.02, "cuda")
+        ref = {}
+        for nm, a, b in (("gate_up", a1, b1), ("down", a2, b2)):
+            for _ in range(3):
+                torch.bmm(a, b)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                torch.bmm(a, b)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / args.steps
+            ref[nm] = {"ms": ms, "TFLOP/s": 2.0 * a.shape[0] * a.shape[1] * a.shape[2] * b.shape[2] / (ms * 1e-3) / 1e12}
+        result["blas_reference"] = {"what": "torch.bmm bf16, %d x [%d rows], no routing raggedness, no SiLU epilogue" % (cfg.E, rows), **ref}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, li)
     print(json.dumps(result))
