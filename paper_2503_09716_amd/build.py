@@ -46,6 +46,13 @@ def build(force: bool = False, verbose: bool = False) -> str:
     objs = [os.path.join(OBJ, s.replace(".hip", ".o")) for s in SOURCES]
     if force or jobs or _stale(LIB, objs):
         run(["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs)
+    # a plain C program that calls the library through include/moe.h (run by the GPU tests)
+    csrc = os.path.join(ROOT, "tests", "c_abi_check.c")
+    cbin = os.path.join(HERE, "c_abi_check")
+    if force or _stale(cbin, [csrc, LIB] + headers):
+        run(["gcc", "-std=c99", "-O1", "-D__HIP_PLATFORM_AMD__", "-I" + os.path.join(ROOT, "include"), "-I/opt/rocm/include",
+             csrc, "-o", cbin, "-L" + HERE, "-lmoe_mi355", "-L/opt/rocm/lib", "-lamdhip64", "-Wl,-rpath,$ORIGIN",
+             "-Wl,-rpath,/opt/rocm/lib"])
     return LIB
 
 
