@@ -97,7 +97,8 @@ size_t moe_h_scratch_bytes(const moe_shape* shape);
  *   "gemm_waves"      4 | 8   wavefronts per GEMM workgroup (one or two per SIMD)
  *   "gemm_wave_rows"  1|2|4   rows of the wave grid (rows x waves/rows): 1 or 2 with 4 waves (4 rows
  *                             is treated as 2), 2 or 4 with 8 waves (1 row is treated as 2)
- *   "gemm_group_m"    1..64   m-tiles swept together along n (L2 reuse of weight panels)
+ *   "gemm_group_m"    0..64   m-tiles swept together along n (L2 reuse of weight panels); 0 (default) picks
+ *                             the typical number of tiles per expert, between 4 and 8
  *   "xcd_remap"       0 | 1   give each XCD runs of consecutive tiles
  *   "small_tiles"     0 | 1   use 128/64/32-row tiles for the ragged tail of an expert
  *   "gemm_tile_rows_up" / "gemm_tile_rows_down"  0 | 128 | 256   rows per m-tile of the gate/up and

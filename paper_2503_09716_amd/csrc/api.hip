@@ -27,7 +27,7 @@ struct ProfRec {
 struct moe_ctx {
     int device = 0;
     char err[512] = {0};
-    GemmConfig gemm{1, 4, 8, 1, 1, 0, 0, -1, -1, 1, 0};
+    GemmConfig gemm{1, 4, 0, 1, 1, 0, 0, -1, -1, 1, 0};
     bool y_fp32 = true;    // dtype of y_perm / y_shared in the staged calls
     int layer_y = -1;      // moe_layer's y_perm: 1 fp32, 0 bf16, -1 choose (its y_shared is always fp32)
     bool out_fp32 = false; // dtype of the layer output
@@ -299,6 +299,16 @@ int pick_tile_rows(const moe_shape& s, int n_tiles, int nseg) {
     return best_tm;
 }
 
+// m-tiles swept together before moving along n.  Tiles of one expert share W panels, so runs
+// that match the typical number of tiles per expert (when that is below 8) keep an XCD's 32
+// concurrent tiles on fewer distinct panels (measured: C4 with 6 instead of 8: down GEMM +2 %).
+int pick_group_m(const moe_ctx* c, const moe_shape& s, int tm) {
+    if (c->gemm.group_m > 0) return c->gemm.group_m;
+    const double per_expert = (double)s.T * s.top_k / ((double)s.E * tm);
+    int g = (int)(per_expert + 0.5);
+    return g < 4 ? 4 : (g > 8 ? 8 : g);
+}
+
 // Which groups one pass of the two GEMMs covers (streamed weights run several passes), and how
 // many m-tiles it can have at most (0 = the bound for any routing).
 struct FfnPass {
@@ -340,7 +350,6 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     memset(&a, 0, sizeof(a));
     a.plan = plan;
     a.T = s.T;
-    a.group_m = c->gemm.group_m;
     a.xcd_remap = c->gemm.xcd_remap;
     a.small_tiles = c->gemm.small_tiles;
     a.out_fp32 = 0;
@@ -349,6 +358,7 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     a.split_rows = 0;
     // GEMM 1: [rows, H] x W1p/W3p [F, H] -> h [rows, F]
     a.descs = descs_up;
+    a.group_m = pick_group_m(c, s, tm_up);
     a.max_mtiles = ps.mtiles_up > 0 ? ps.mtiles_up : (int)max_mtiles(s, tm_up);
     a.a_routed = (const char*)(x_perm_tiled ? x_perm_tiled : (row_token ? x : x_perm));
     a.a_shared = (const char*)x;
@@ -372,6 +382,7 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     }
     // GEMM 2: h [rows, F] x W2p [H, F] -> y [rows, H]
     a.descs = descs_down;
+    a.group_m = pick_group_m(c, s, tm_down);
     a.max_mtiles = (ps.mtiles_down > 0 ? ps.mtiles_down : (int)max_mtiles(s, tm_down)) + s.E * (dsp - 1);
     a.a_routed = (const char*)h;
     a.a_shared = (const char*)h + Rpad * s.F * 2;
@@ -517,7 +528,7 @@ moe_status moe_set_option(moe_ctx* c, const char* key, int32_t v) {
     c->err[0] = 0;
     if (!strcmp(key, "gemm_wave_rows") && (v == 1 || v == 2 || v == 4)) { c->gemm.wave_rows = v; return MOE_OK; }
     if (!strcmp(key, "gemm_waves") && (v == 4 || v == 8)) { c->gemm.waves = v; return MOE_OK; }
-    if (!strcmp(key, "gemm_group_m") && v >= 1 && v <= 64) { c->gemm.group_m = v; return MOE_OK; }
+    if (!strcmp(key, "gemm_group_m") && v >= 0 && v <= 64) { c->gemm.group_m = v; return MOE_OK; }
     if (!strcmp(key, "xcd_remap") && (v == 0 || v == 1)) { c->gemm.xcd_remap = v; return MOE_OK; }
     if (!strcmp(key, "small_tiles") && (v == 0 || v == 1)) { c->gemm.small_tiles = v; return MOE_OK; }
     if (!strcmp(key, "gemm_tile_rows_up") && (v == 0 || v == 128 || v == 256)) { c->gemm.tile_rows_up = v; return MOE_OK; }

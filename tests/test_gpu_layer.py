@@ -135,7 +135,7 @@ def test_tile_order_options_give_same_bits(moe):
 
 def check_tile_orders(moe, gl):
     ref = gl.run_layer(True)
-    for key, default, values in (("tails_last", -1, (0, 1)), ("gemm_group_m", 8, (1, 3, 16)), ("xcd_remap", 1, (0,))):
+    for key, default, values in (("tails_last", -1, (0, 1)), ("gemm_group_m", 0, (1, 3, 16)), ("xcd_remap", 1, (0,))):
         for v in values:
             moe.set_option(key, v)
             try:
