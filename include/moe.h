@@ -119,8 +119,9 @@ size_t moe_h_scratch_bytes(const moe_shape* shape);
  *                             traffic of the down projection's store and of the combine's loads, but
  *                             rounds each expert output to 8 mantissa bits before the weighted sum
  *   "layer_y_fp32"    -1|0|1  moe_layer: dtype of its internal y_perm: 1 fp32, 0 bf16, -1 (default) bf16 when
- *                             top_k >= 4 (each rounded term then carries a small share of the sum), fp32
- *                             otherwise.  Its y_shared is always fp32.
+ *                             top_k >= 4 and shared experts exist (each rounded term then carries a small
+ *                             share of the output), fp32 otherwise.
+ *                             Its y_shared is always fp32.
  *   "out_fp32"        0 | 1   dtype of the layer output written by moe_combine / moe_layer:
  *                             0 (default) bf16 = round-to-nearest-even of the fp32 sum, 1 fp32 */
 moe_status moe_set_option(moe_ctx* ctx, const char* key, int32_t value);

@@ -454,11 +454,12 @@ moe_status run_front(moe_ctx* c, const moe_shape& s, const void* x, const void* 
         f->x_tiled = w8 + L.x_tiled;
     }
     // y_perm in bf16 halves the down projection's stores and the combine's loads.  Its rounding
-    // moves out[t] by at most sum_j w_j * 2^-8 * |y_j|; with k >= 4 routed terms that share a
-    // total weight <= 1 this stays far below the error bar (measured at full size: see the
-    // tests), with k = 2 it would use up most of it, so fp32 is kept there.  y_shared (weight 1)
-    // is always fp32.
-    f->y32 = c->layer_y >= 0 ? c->layer_y != 0 : s.top_k < 4;
+    // moves out[t] by at most sum_j w_j * 2^-8 * |y_j|.  Chosen when that is small against the
+    // output: at least 4 routed terms next to shared experts of weight 1, which then carry most
+    // of the output (measured at full size: no change of the error).  Without shared experts the
+    // routed terms are the whole output and their rounding would use up most of the error bar
+    // whatever their weights: fp32 there.  y_shared (weight 1) is always fp32.
+    f->y32 = c->layer_y >= 0 ? c->layer_y != 0 : !(s.top_k >= 4 && s.num_shared > 0);
     return MOE_OK;
 }
 

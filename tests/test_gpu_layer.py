@@ -270,3 +270,21 @@ def test_layer_in_a_hip_graph(moe):
         assert torch.equal(out, ref)
         eager = gl.run_layer()             # the library's own eager work between replays
         assert torch.equal(eager, ref)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_layer_random_small_shapes(moe, seed):
+    """Seeded random shapes (ragged T, odd expert counts, k up to E, 0-3 shared experts, widths
+    that are odd multiples of 64) through moe_layer, every token against the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    E = int(rng.integers(1, 41))
+    k = int(rng.integers(1, min(E, 8) + 1))
+    cfg = scaled_config(
+        "C4" if seed % 2 else "C2",
+        T=int(rng.integers(1, 700)), H=64 * int(rng.integers(1, 7)), F=64 * int(rng.integers(1, 9)),
+        E=E, top_k=k, num_shared=int(rng.integers(0, 4)) if seed % 2 else 0,
+        bias=["none", "normal", "logzipf_rank"][seed % 3])
+    say("random", cfg)
+    gl = P.GpuLayer(moe, make_layer_inputs(cfg, device="cuda"))
+    out, out16 = gl.run_layer_both()
+    say(json.dumps(P.check_layer_against_oracle(gl, out, out16=out16)))
