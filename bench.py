@@ -53,6 +53,9 @@ def main():
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--option", action="append", default=[], help="library tuning knob key=value")
+    ap.add_argument("--max-tokens-per-pass", type=int, default=0, metavar="B_E",
+                    help="also time moe_layer_chunked with this many tokens per pass (workspace sized for one pass) "
+                         "and report it in a 'chunked' object")
     ap.add_argument("--streamed", type=int, default=0, metavar="G",
                     help="also time moe_layer_streamed (expert weights in pinned host memory, G experts per group, "
                          "two staging slots) and report it in a 'streamed' object")
@@ -159,6 +162,21 @@ def main():
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
                      "avg_launch_ms": g1_ms, "flops_per_launch": flops_g1},
     }
+    if args.max_tokens_per_pass:
+        be = min(args.max_tokens_per_pass, cfg.T)
+        from dataclasses import replace
+        ws_pass = moe.new_workspace(shape_of(replace(cfg, T=be)))
+        for _ in range(3):
+            moe.layer_chunked(shape, li.x, li.wg, bias, w1p, w3p, w2p, be, out, ws_pass, tables=tables)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            moe.layer_chunked(shape, li.x, li.wg, bias, w1p, w3p, w2p, be, out, ws_pass, tables=tables)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / args.steps * 1e3
+        result["chunked"] = {"max_tokens_per_pass": be, "passes": -(-cfg.T // be), "ms_per_step": ms,
+                             "tokens/s": cfg.T / (ms * 1e-3), "workspace_bytes": ws_pass.numel(),
+                             "workspace_bytes_unchunked": ws.numel()}
     if args.streamed:
         G = args.streamed
         host = [[w.cpu().pin_memory() for w in ws_] for ws_ in (w1p, w3p, w2p)]

@@ -200,6 +200,25 @@ moe_status moe_layer(moe_ctx* ctx, const moe_shape* shape, const void* x_bf16, c
                      const void* const* w2p, void* out, void* workspace, size_t workspace_bytes,
                      void* hip_stream);
 
+/* Accumulation of micro-batches (Sec. 4.2: the hidden states that leave attention in micro-batches
+ * of b_a sequences are accumulated until the expert module's batch B is reached): appends
+ * `rows` rows of x_microbatch [rows, H] bf16 (device) to staging [capacity_rows, H] bf16 (device)
+ * at row *rows_filled and adds `rows` to *rows_filled (host counter owned by the caller).
+ * An asynchronous device-to-device copy on hip_stream.  MOE_E_ARG if the rows do not fit. */
+moe_status moe_accumulate(moe_ctx* ctx, void* staging, int32_t capacity_rows, int32_t H, int32_t* rows_filled,
+                          const void* x_microbatch, int32_t rows, void* hip_stream);
+
+/* moe_layer over at most max_tokens_per_pass tokens at a time (Sec. 4.3: the expert module
+ * takes b_e tokens per pass so that its intermediates fit the memory left beside weights and
+ * KV cache).  Tokens are independent, so the result equals moe_layer's: bit for bit with option
+ * "down_tail_splits" = 0, otherwise up to the summation order of rows that fall into a K-split
+ * tail tile in one run and not in the other.  `shape` describes all T tokens; the workspace only
+ * has to hold one pass: moe_workspace_bytes of the same shape with T = min(T, max_tokens_per_pass). */
+moe_status moe_layer_chunked(moe_ctx* ctx, const moe_shape* shape, const void* x_bf16, const void* wg_bf16,
+                             const float* gate_bias, const void* const* w1p, const void* const* w3p,
+                             const void* const* w2p, int32_t max_tokens_per_pass, void* out, void* workspace,
+                             size_t workspace_bytes, void* hip_stream);
+
 /* moe_layer with the expert weights in HOST memory (Sec. 4.2: experts are executed one after
  * another while the next expert's weights are prefetched into a second buffer; App. A: only
  * experts that received tokens are fetched).  Experts are taken in groups of

@@ -20,7 +20,7 @@ STAGES = ["route", "permute_index", "permute_gather", "plan", "ffn_gate_up", "ff
 EXPORTS = [
     "moe_create", "moe_destroy", "moe_last_error", "moe_workspace_bytes", "moe_h_scratch_bytes", "moe_set_option", "moe_pack_weight",
     "moe_route", "moe_permute", "moe_grouped_ffn", "moe_combine", "moe_layer", "moe_layer_views",
-    "moe_layer_streamed", "moe_stream_stats", "moe_estimate_streamed_ms",
+    "moe_layer_streamed", "moe_stream_stats", "moe_estimate_streamed_ms", "moe_accumulate", "moe_layer_chunked",
     "moe_profile_enable", "moe_profile_read",
 ]
 
@@ -69,6 +69,8 @@ def load_library():
     lib.moe_layer.argtypes = [C.c_void_p, sp, vp, vp, f32p, tab, tab, tab, vp, vp, C.c_size_t, vp]
     lib.moe_layer_streamed.argtypes = [C.c_void_p, sp, vp, vp, f32p, tab, tab, tab, vp, C.c_size_t, C.c_int32, C.c_int32,
                                        vp, vp, C.c_size_t, vp]
+    lib.moe_accumulate.argtypes = [C.c_void_p, vp, C.c_int32, C.c_int32, C.POINTER(C.c_int32), vp, C.c_int32, vp]
+    lib.moe_layer_chunked.argtypes = [C.c_void_p, sp, vp, vp, f32p, tab, tab, tab, C.c_int32, vp, vp, C.c_size_t, vp]
     lib.moe_stream_stats.argtypes = [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.moe_layer_views.argtypes = [sp, vp, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
                                     C.POINTER(C.c_void_p)]
@@ -217,6 +219,19 @@ class Moe:
                                                 host_table(host_w1p), host_table(host_w3p), host_table(host_w2p),
                                                 _ptr(slots), slot_bytes, num_slots, experts_per_group, _ptr(out),
                                                 _ptr(workspace), workspace.numel(), _stream()))
+
+    def layer_chunked(self, shape, x, wg, bias, w1p, w3p, w2p, max_tokens_per_pass, out, workspace, tables=None):
+        t1, t3, t2 = tables if tables is not None else (_table(w1p), _table(w3p), _table(w2p))
+        self._check(self.lib.moe_layer_chunked(self.h, C.byref(shape), _ptr(x), _ptr(wg), _ptr(bias), t1, t3, t2,
+                                               max_tokens_per_pass, _ptr(out), _ptr(workspace), workspace.numel(),
+                                               _stream()))
+
+    def accumulate(self, staging, rows_filled: int, x_microbatch) -> int:
+        """Appends x_microbatch's rows to staging at row rows_filled; returns the new fill count."""
+        n = C.c_int32(rows_filled)
+        self._check(self.lib.moe_accumulate(self.h, _ptr(staging), staging.shape[0], staging.shape[1], C.byref(n),
+                                            _ptr(x_microbatch), x_microbatch.shape[0], _stream()))
+        return n.value
 
     def stream_stats(self):
         b, g, k = C.c_uint64(), C.c_int32(), C.c_int32()

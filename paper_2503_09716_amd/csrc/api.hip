@@ -634,6 +634,38 @@ moe_status moe_layer(moe_ctx* c, const moe_shape* s, const void* x, const void* 
     return MOE_OK;
 }
 
+moe_status moe_accumulate(moe_ctx* c, void* staging, int32_t capacity, int32_t H, int32_t* filled, const void* x_mb,
+                          int32_t rows, void* stream) {
+    if (!c) return MOE_E_ARG;
+    c->err[0] = 0;
+    if (!staging || !filled || !x_mb || rows < 0 || H < 1 || capacity < 0) return fail(c, MOE_E_ARG, "accumulate: bad argument");
+    if (*filled < 0 || (int64_t)*filled + rows > capacity)
+        return fail(c, MOE_E_ARG, "accumulate: %d rows do not fit (%d of %d filled)", rows, *filled, capacity);
+    HIP_TRY(c, hipSetDevice(c->device));
+    if (rows > 0)
+        HIP_TRY(c, hipMemcpyAsync((char*)staging + (size_t)*filled * H * 2, x_mb, (size_t)rows * H * 2, hipMemcpyDeviceToDevice,
+                                  (hipStream_t)stream));
+    *filled += rows;
+    return MOE_OK;
+}
+
+moe_status moe_layer_chunked(moe_ctx* c, const moe_shape* s, const void* x, const void* wg, const float* bias,
+                             const void* const* w1p, const void* const* w3p, const void* const* w2p, int32_t max_tokens,
+                             void* out, void* ws, size_t ws_bytes, void* stream) {
+    if (moe_status st = check_common(c, s)) return st;
+    if (max_tokens < 1) return fail(c, MOE_E_ARG, "layer_chunked: max_tokens_per_pass must be >= 1");
+    if (!x || !out) return fail(c, MOE_E_ARG, "layer_chunked: NULL pointer");
+    const size_t out_row = (size_t)s->H * (c->out_fp32 ? 4 : 2);
+    for (int t0 = 0; t0 < s->T; t0 += max_tokens) {
+        moe_shape part = *s;
+        part.T = s->T - t0 < max_tokens ? s->T - t0 : max_tokens;
+        if (moe_status st = moe_layer(c, &part, (const char*)x + (size_t)t0 * s->H * 2, wg, bias, w1p, w3p, w2p,
+                                      (char*)out + (size_t)t0 * out_row, ws, ws_bytes, stream))
+            return st;
+    }
+    return MOE_OK;
+}
+
 moe_status moe_layer_streamed(moe_ctx* c, const moe_shape* s, const void* x, const void* wg, const float* bias,
                               const void* const* hw1, const void* const* hw3, const void* const* hw2, void* slots,
                               size_t slot_bytes, int32_t num_slots, int32_t per_group, void* out, void* ws,

@@ -551,7 +551,10 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
         // A tail higher than half a tile runs the full-height variant and takes as long as a full
         // tile, so it stays with its group (keeps the group's W panels shared and the CUs in
         // step); only a short tail is moved to the end of the list.
-        const bool moved = tails_last && blocks > 0 && small_tiles && blocks * 64 <= tm;
+        // (A shared expert's tail is not moved in a down list with K pieces: the pieces' partial
+        // sums are reduced into y_perm, while shared rows belong to y_shared.)
+        const bool moved = tails_last && blocks > 0 && small_tiles && blocks * 64 <= tm &&
+                           !(which == 1 && down_splits > 1 && group >= E);
         const int nrun = nfull + (blocks > 0 && !moved);   // tiles listed in group order
         __syncthreads();
         first[tid] = nrun;

@@ -288,3 +288,75 @@ def test_layer_random_small_shapes(moe, seed):
     gl = P.GpuLayer(moe, make_layer_inputs(cfg, device="cuda"))
     out, out16 = gl.run_layer_both()
     say(json.dumps(P.check_layer_against_oracle(gl, out, out16=out16)))
+
+
+@pytest.mark.parametrize("T,F,E,Ns", [(132, 512, 12, 2), (900, 512, 12, 2), (260, 1024, 4, 1), (516, 2048, 8, 3),
+                                       (131, 512, 32, 1), (1, 512, 2, 1)])
+def test_layer_short_shared_tail_next_to_k_split_tails(moe, T, F, E, Ns):
+    """Shapes where the down projection cuts short routed tails along K (at most 32 experts,
+    F/64 >= 8) AND the shared experts' T rows end in a short tail of their own: that tail must
+    land in y_shared, whole, while the routed pieces are reduced into y_perm.  Every token
+    against the oracle."""
+    cfg = scaled_config("C4", T=T, H=256, F=F, E=E, top_k=min(4, E), num_shared=Ns)
+    say("shared tail", cfg)
+    gl = P.GpuLayer(moe, make_layer_inputs(cfg, device="cuda"))
+    out, out16 = gl.run_layer_both()
+    say(json.dumps(P.check_layer_against_oracle(gl, out, out16=out16)))
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_layer_random_k_split_shapes(moe, seed):
+    """Seeded random shapes inside the K-split-tail regime (E <= 32, F a multiple of 128 from 512
+    up), with and without shared experts, every token against the oracle."""
+    rng = np.random.default_rng(5000 + seed)
+    E = int(rng.integers(1, 33))
+    cfg = scaled_config(
+        "C4" if seed % 3 else "C2",
+        T=int(rng.integers(1, 1200)), H=64 * int(rng.integers(1, 5)), F=128 * int(rng.integers(4, 13)),
+        E=E, top_k=int(rng.integers(1, min(E, 6) + 1)), num_shared=int(rng.integers(1, 4)) if seed % 3 else 0,
+        bias=["none", "normal", "logzipf_rank"][seed % 3])
+    say("random k-split", cfg)
+    gl = P.GpuLayer(moe, make_layer_inputs(cfg, device="cuda"))
+    out, out16 = gl.run_layer_both()
+    say(json.dumps(P.check_layer_against_oracle(gl, out, out16=out16)))
+
+
+def test_accumulate_then_chunked_layer(moe):
+    """Micro-batches accumulated into a staging tensor, then the layer run b_e tokens at a time
+    with a workspace sized for one pass: same bits as one moe_layer call over all tokens (K-split
+    tails off), and within the error bar of it with the default options."""
+    from paper_2503_09716_amd import MoeError, shape_of
+    cfg = scaled_config("C4", T=900, H=256, F=512, E=12, top_k=4)
+    gl = P.GpuLayer(moe, make_layer_inputs(cfg, device="cuda"), host_weights=False)
+    staging = torch.zeros((cfg.T, cfg.H), dtype=torch.bfloat16, device="cuda")
+    filled = 0
+    for lo in range(0, cfg.T, 128):                      # micro-batches of 128 rows, the last one ragged
+        filled = moe.accumulate(staging, filled, gl.x[lo:lo + 128].contiguous())
+    assert filled == cfg.T
+    torch.cuda.synchronize()
+    assert torch.equal(staging, gl.x)
+    with pytest.raises(MoeError):
+        moe.accumulate(staging, filled, gl.x[:1].contiguous())
+    be = 384
+    ws_small = moe.new_workspace(shape_of(scaled_config("C4", T=be, H=256, F=512, E=12, top_k=4)))
+    assert ws_small.numel() < gl.ws.numel()
+    out_c = torch.empty((cfg.T, cfg.H), dtype=torch.float32, device="cuda")
+    moe.set_option("out_fp32", 1)
+    try:
+        for splits in (0, 1):
+            moe.set_option("down_tail_splits", splits)
+            ref = torch.empty_like(out_c)
+            moe.layer(gl.shape, staging, gl.wg, gl.bias, gl.w1p, gl.w3p, gl.w2p, ref, gl.ws, tables=gl.tables)
+            moe.layer_chunked(gl.shape, staging, gl.wg, gl.bias, gl.w1p, gl.w3p, gl.w2p, be, out_c, ws_small,
+                              tables=gl.tables)
+            torch.cuda.synchronize()
+            if splits == 0:
+                assert torch.equal(ref, out_c)
+            else:
+                # bf16 y_perm (k = 4 next to shared experts): a changed summation order can move
+                # a routed term by one bf16 step, far below the error bar
+                rms = ref.double().pow(2).mean().sqrt().item()
+                assert (ref - out_c).abs().max().item() <= 4e-3 * rms
+    finally:
+        moe.set_option("out_fp32", 0)
+        moe.set_option("down_tail_splits", 1)
