@@ -321,6 +321,67 @@ def test_layer_random_k_split_shapes(moe, seed):
     say(json.dumps(P.check_layer_against_oracle(gl, out, out16=out16)))
 
 
+OPTION_DEFAULTS = {"tails_last": -1, "gemm_group_m": 0, "xcd_remap": 1, "x_tiled": -1, "small_tiles": 1,
+                   "gemm_tile_rows_up": 0, "gemm_tile_rows_down": 0, "gemm_waves": 4, "gemm_wave_rows": 1}
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_layer_fuzz_entry_points_and_options(moe, seed):
+    """One seeded random shape per case (half of them inside the K-split-tail regime):
+    (1) moe_layer against the oracle, every token;
+    (2) moe_layer_streamed with a random group size and slot count gives the same bits;
+    (3) with K-split tails off, a random draw of the tile-shape / tile-order options and
+        moe_layer_chunked with a random pass size give the same bits as the default options
+        (none of them changes the order in which any output element is summed)."""
+    rng = np.random.default_rng(9000 + seed)
+    E = int(rng.integers(1, 41))
+    wide = seed % 2 == 0
+    cfg = scaled_config(
+        "C4" if seed % 4 >= 2 else "C2",
+        T=int(rng.integers(1, 1400)), H=64 * int(rng.integers(1, 5)),
+        F=128 * int(rng.integers(4, 11)) if wide else 64 * int(rng.integers(1, 8)),
+        E=E, top_k=int(rng.integers(1, min(E, 6) + 1)), num_shared=int(rng.integers(0, 4)) if seed % 4 >= 2 else 0,
+        bias=["none", "normal", "logzipf_rank"][seed % 3])
+    say("fuzz", cfg)
+    gl = P.GpuLayer(moe, make_layer_inputs(cfg, device="cuda"))
+    out, out16 = gl.run_layer_both()
+    say(json.dumps(P.check_layer_against_oracle(gl, out, out16=out16)))
+
+    per_group, num_slots = int(rng.integers(1, min(E, 8) + 1)), int(rng.integers(2, 5))
+    host = [[w.cpu().pin_memory() for w in ws] for ws in (gl.w1p, gl.w3p, gl.w2p)]
+    slots = torch.empty(num_slots * max(per_group, cfg.num_shared) * 3 * cfg.H * cfg.F * 2, dtype=torch.uint8, device="cuda")
+    got = torch.full_like(out, float("nan"))
+    opts = {k: int(rng.choice(v)) for k, v in (
+        ("tails_last", (0, 1)), ("gemm_group_m", (0, 1, 5, 16)), ("xcd_remap", (0, 1)), ("x_tiled", (0, 1)),
+        ("small_tiles", (0, 1)), ("gemm_tile_rows_up", (0, 128, 256)), ("gemm_tile_rows_down", (0, 128, 256)))}
+    opts["gemm_waves"], opts["gemm_wave_rows"] = [(4, 1), (4, 2), (8, 2), (8, 4)][int(rng.integers(0, 4))]
+    be = int(rng.integers(1, cfg.T + 1))
+    say("streamed", per_group, num_slots, "options", opts, "tokens per pass", be)
+    moe.set_option("out_fp32", 1)
+    try:
+        moe.layer_streamed(gl.shape, gl.x, gl.wg, gl.bias, host[0], host[1], host[2], slots, num_slots, per_group, got, gl.ws)
+        torch.cuda.synchronize()
+        assert torch.equal(out, got), "streamed"
+        moe.set_option("down_tail_splits", 0)
+        ref0 = torch.empty_like(out)
+        moe.layer(gl.shape, gl.x, gl.wg, gl.bias, gl.w1p, gl.w3p, gl.w2p, ref0, gl.ws, tables=gl.tables)
+        got.fill_(float("nan"))
+        moe.layer_chunked(gl.shape, gl.x, gl.wg, gl.bias, gl.w1p, gl.w3p, gl.w2p, be, got, gl.ws, tables=gl.tables)
+        torch.cuda.synchronize()
+        assert torch.equal(ref0, got), "chunked"
+        for k, v in opts.items():
+            moe.set_option(k, v)
+        got.fill_(float("nan"))
+        moe.layer(gl.shape, gl.x, gl.wg, gl.bias, gl.w1p, gl.w3p, gl.w2p, got, gl.ws, tables=gl.tables)
+        torch.cuda.synchronize()
+        assert torch.equal(ref0, got), "options"
+    finally:
+        for k, v in OPTION_DEFAULTS.items():
+            moe.set_option(k, v)
+        moe.set_option("down_tail_splits", 1)
+        moe.set_option("out_fp32", 0)
+
+
 def test_accumulate_then_chunked_layer(moe):
     """Micro-batches accumulated into a staging tensor, then the layer run b_e tokens at a time
     with a workspace sized for one pass: same bits as one moe_layer call over all tokens (K-split
