@@ -382,6 +382,56 @@ def test_layer_fuzz_entry_points_and_options(moe, seed):
         moe.set_option("out_fp32", 0)
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_staged_calls_fuzz_equal_fused_layer(moe, seed):
+    """moe_route -> moe_permute -> moe_grouped_ffn -> moe_combine on seeded random shapes give the
+    bits of moe_layer (y_perm in fp32 on both sides), with the rows either gathered into x_perm
+    by moe_permute or gathered by the GEMM itself through row_token."""
+    rng = np.random.default_rng(7000 + seed)
+    E = int(rng.integers(1, 49))
+    cfg = scaled_config(
+        "C4" if seed % 2 else "C2",
+        T=int(rng.integers(1, 1100)), H=64 * int(rng.integers(1, 5)), F=64 * int(rng.integers(1, 17)),
+        E=E, top_k=int(rng.integers(1, min(E, 8) + 1)), num_shared=int(rng.integers(0, 4)) if seed % 2 else 0,
+        bias=["none", "normal", "logzipf_rank"][seed % 3])
+    use_row_token = bool(seed % 4 < 2)
+    say("staged fuzz", cfg, "row_token" if use_row_token else "x_perm")
+    gl = P.GpuLayer(moe, make_layer_inputs(cfg, device="cuda"), host_weights=False)
+    sh, dev, R = gl.shape, "cuda", cfg.T * cfg.top_k
+    moe.set_option("layer_y_fp32", 1)
+    moe.set_option("y_fp32", 1)
+    try:
+        out = gl.run_layer(True)
+        moe.set_option("out_fp32", 1)
+        idx = torch.empty((cfg.T, cfg.top_k), dtype=torch.int32, device=dev)
+        w = torch.empty((cfg.T, cfg.top_k), dtype=torch.float32, device=dev)
+        ws = moe.new_workspace(sh)
+        moe.route(sh, gl.x, gl.wg, gl.bias, idx, w, None, ws)
+        x_perm = torch.empty((R, cfg.H), dtype=torch.bfloat16, device=dev)
+        off = torch.empty(cfg.E + 1, dtype=torch.int32, device=dev)
+        perm = torch.empty(R, dtype=torch.int32, device=dev)
+        inv, rtok = torch.empty_like(perm), torch.empty_like(perm)
+        moe.permute(sh, gl.x, idx, x_perm, off, perm, inv, rtok, ws)
+        h = moe.new_h_scratch(sh)
+        y = torch.full((R, cfg.H), float("nan"), dtype=torch.float32, device=dev)
+        ysh = torch.full((cfg.T, cfg.H), float("nan"), dtype=torch.float32, device=dev) if cfg.num_shared else None
+        moe.grouped_ffn(sh, None if use_row_token else x_perm, rtok if use_row_token else None, gl.x, off,
+                        gl.w1p, gl.w3p, gl.w2p, h, y, ysh, ws)
+        out2 = torch.empty_like(out)
+        moe.combine(sh, y, inv, w, ysh, out2)
+        torch.cuda.synchronize()
+    finally:
+        moe.set_option("layer_y_fp32", -1)
+        moe.set_option("out_fp32", 0)
+    assert torch.equal(out, out2)
+    v = moe.layer_views(sh, gl.ws)
+    assert torch.equal(v["topk_idx"], idx) and torch.equal(v["topk_w"], w)
+    assert torch.equal(v["expert_offsets"], off) and torch.equal(v["inv_perm"], inv)
+    # x_perm is the gather the permutation defines
+    assert torch.equal(x_perm, gl.x[rtok.long()])
+    assert torch.equal(rtok, perm // cfg.top_k)
+
+
 def test_accumulate_then_chunked_layer(moe):
     """Micro-batches accumulated into a staging tensor, then the layer run b_e tokens at a time
     with a workspace sized for one pass: same bits as one moe_layer call over all tokens (K-split
