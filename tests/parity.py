@@ -181,15 +181,21 @@ def check_layer_against_oracle(gl: GpuLayer, out: torch.Tensor, tokens=None, che
 
 
 def sample_tokens(idx: np.ndarray, E: int, n: int, seed: int) -> np.ndarray:
-    """n tokens: one routed to each non-empty expert, the rest uniformly at random."""
+    """About n tokens: for each non-empty expert one at random plus the ones behind the first and
+    the last row of its group (the last row sits in the group's tail tile), the first and the last
+    16 tokens (the tail tile of the shared experts), the rest uniformly at random."""
     rng = np.random.default_rng(seed)
     T = idx.shape[0]
-    chosen = []
     flat_tok = np.repeat(np.arange(T), idx.shape[1])
     flat_e = idx.reshape(-1)
     order = rng.permutation(len(flat_e))
     seen = np.full(E, -1, np.int64)
     seen[flat_e[order]] = flat_tok[order]
-    chosen = [int(t) for t in seen if t >= 0]
-    rest = rng.permutation(T)[:max(0, n - len(chosen))]
-    return np.unique(np.concatenate([np.array(chosen, np.int64), rest])).astype(np.int32)
+    first = np.full(E, -1, np.int64)
+    last = np.full(E, -1, np.int64)
+    last[flat_e] = flat_tok                    # rows of a group are in token order: highest token = last row
+    first[flat_e[::-1]] = flat_tok[::-1]
+    chosen = np.concatenate([seen, first, last, np.arange(min(16, T)), np.arange(max(0, T - 16), T)])
+    chosen = chosen[chosen >= 0]
+    rest = rng.permutation(T)[:max(0, n - len(np.unique(chosen)))]
+    return np.unique(np.concatenate([chosen, rest])).astype(np.int32)

@@ -160,7 +160,7 @@ def test_layer_metamorphic_exact(moe):
     assert (z.float() == 0).all()
 
 
-FULL = [("C2", 96), ("C3", 64), ("C4", 160), ("C5", 224), ("C5b", 64)]
+FULL = [("C2", 512), ("C3", 384), ("C4", 768), ("C5", 1024), ("C5b", 384)]
 
 
 @pytest.mark.parametrize("name,nsample", FULL)
