@@ -195,6 +195,27 @@ def test_layer_full_size_sampled(moe, name, nsample):
         json.dump(rep, f)
 
 
+def test_layer_at_the_4_gib_limit(moe):
+    """Largest permuted batch the library takes for H = 2048 (x_perm just under 4 GiB, the limit of
+    one buffer descriptor; fp32 y_perm is then 8.6 GB, beyond 32-bit byte offsets): sampled tokens,
+    among them the last rows of every group, against the oracle.  One row more is refused."""
+    from paper_2503_09716_amd import MoeError, shape_of
+    cfg = scaled_config("C2", T=524_000, H=2048, F=64, E=8, top_k=2)
+    assert cfg.T * cfg.top_k * cfg.H * 2 < 2 ** 32 <= (cfg.T + 288) * cfg.top_k * cfg.H * 2
+    say("limit", cfg)
+    gl = P.GpuLayer(moe, make_layer_inputs(cfg, device="cuda"))
+    out, out16 = gl.run_layer_both()
+    assert torch.isfinite(out).all()
+    idx = moe.layer_views(gl.shape, gl.ws)["topk_idx"].cpu().numpy()
+    tokens = P.sample_tokens(idx, cfg.E, 256, cfg.seed)
+    say(json.dumps(P.check_layer_against_oracle(gl, out, tokens=tokens, check_all_routing=False, out16=out16)))
+    too_big = shape_of(scaled_config("C2", T=cfg.T + 288, H=2048, F=64, E=8, top_k=2))
+    from paper_2503_09716_amd.binding import workspace_bytes
+    assert workspace_bytes(too_big) == 0
+    with pytest.raises(MoeError):
+        moe.layer(too_big, gl.x, gl.wg, gl.bias, gl.w1p, gl.w3p, gl.w2p, out, gl.ws, tables=gl.tables)
+
+
 STREAMED = [
     # name, overrides, experts per group, slots
     ("C2", dict(T=600, H=256, F=448), 1, 2),                    # one expert at a time, double buffer
