@@ -140,8 +140,23 @@ def main():
         "permute_gather": gather_bytes if stage_ms["permute_gather"] > 0 else None,
         "combine": R * cfg.H * 4 + Rs * 0 + (cfg.T * cfg.H * 4 if cfg.num_shared else 0) + 8 * R + cfg.T * cfg.H * 2,
     }
-    hbm_stages = {k: {"bytes": v, "GB/s": v / (stage_ms[k] * 1e-3) / 1e9, "frac_of_8TB/s": v / (stage_ms[k] * 1e-3) / 1e9 / PEAK_HBM_GBS}
+    # measured ceiling beside the published one: a plain device-to-device copy of 1 GiB (read + write bytes)
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        dst.copy_(src)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ev[0].record()
+    for _ in range(5):
+        dst.copy_(src)
+    ev[1].record()
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2 * src.numel() / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9
+    del src, dst
+    hbm_stages = {k: {"bytes": v, "GB/s": v / (stage_ms[k] * 1e-3) / 1e9, "frac_of_8TB/s": v / (stage_ms[k] * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                      "frac_of_device_copy": v / (stage_ms[k] * 1e-3) / 1e9 / copy_gbs}
                   for k, v in hbm.items() if v and stage_ms[k] > 0}
+    hbm_stages["device_copy_1GiB_GB/s"] = copy_gbs
 
     result = {
         "metric": "expert-module tokens/s and grouped-FFN TFLOP/s (% bf16 MFMA peak), 1 GPU",

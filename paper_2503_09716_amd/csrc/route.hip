@@ -4,7 +4,7 @@
 // bf16 x bf16 products are exact in fp32, so the GPU logits differ from a correctly rounded
 // reference only through the order of the fp32 additions; both paths below keep the sums short
 // enough that top-k agrees except at genuine near-ties.
-//   E <= 16 : one streaming kernel (HBM-bound): fp32 FMAs per lane, butterfly reduction.
+//   E <= 16 : one streaming kernel (HBM-bound): fp32 FMAs per lane, reduction over lanes and waves.
 //   E  > 16 : the logits are a dense contraction and go through the MFMA tile routine of the
 //             grouped GEMM (x against the packed gate matrix, K cut into independent chains);
 //             route_topk_kernel then sums the partials, adds the bias and selects.
@@ -87,38 +87,58 @@ __device__ __forceinline__ void route_finish(const float (&v)[NV], const int lan
     }
 }
 
-// Few experts (E <= 16): HBM-bound.  One wavefront takes SMALL_TOK tokens; lane l owns the hidden
-// elements h = 512*it + 8*l .. +7, so a wave reads 1 KiB of each token row per step and the
-// matching 8 rows of Wg (8*E contiguous bf16, cache resident).  Per-lane partial sums are
-// combined by a butterfly, after which every lane holds every logit.
-constexpr int SMALL_TOK = 4;
+// Sum over the 64 lanes of N per-lane values (N = 64 or 128) in N - N/64 exchange steps instead
+// of 6N: at the step with lane mask m every lane keeps one half of its values (upper half if its
+// bit m is set) and adds the partner's copy of that half.  Afterwards lane l holds the complete
+// sums of values l*(N/64) .. +N/64-1 in v[0..N/64).  fp32 addition is commutative, so every value
+// is added up along the same tree of lanes whatever its index.
+template <int N, int HALF = N / 2, int MASK = 32>
+__device__ __forceinline__ void lane_reduce_scatter(float (&v)[N], const int lane) {
+    const bool up = (lane & MASK) != 0;
+#pragma unroll
+    for (int i = 0; i < HALF; ++i) {
+        const float keep = up ? v[i + HALF] : v[i];
+        const float send = up ? v[i] : v[i + HALF];
+        v[i] = keep + __shfl_xor(send, MASK, 64);
+    }
+    if constexpr (MASK > 1) lane_reduce_scatter<N, HALF / 2, MASK / 2>(v, lane);
+}
 
-template <int EP, bool EXACT>  // EP: padded expert count (8 or 16); EXACT: E == EP, rows of Wg are 16-byte vectors
+// Few experts (E <= 16): HBM-bound.  One workgroup of 4 wavefronts takes TOK tokens; every wave
+// works on all TOK tokens but only on a quarter of the hidden dimension (thread i owns
+// h = 2048*it + 8*i .. +7), so a wave has TOK 16-byte loads in flight per step and reads a quarter
+// of Wg (8*E contiguous bf16 per 8 hidden elements, cache resident).  The per-lane partial sums
+// go through lane_reduce_scatter, the four waves' results through LDS (added in wave order), and
+// each wave then finishes TOK/4 tokens.  The sum that makes a logit does not depend on TOK, on
+// the token's slot in the workgroup or on T.
+template <int EP, bool EXACT, int TOK>  // EP: padded expert count (8 or 16); EXACT: E == EP, rows of Wg are 16-byte vectors
 __global__ __launch_bounds__(256) void route_small_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ wg,
                                                           const float* __restrict__ bias, int T, int H, int E, int k,
                                                           int renorm, float scale, int32_t* __restrict__ idx_out,
                                                           float* __restrict__ w_out, float* __restrict__ logits_out) {
+    constexpr int NVAL = TOK * EP;   // 64 or 128
+    constexpr int PER = NVAL / 64;
+    static_assert(NVAL == 64 || NVAL == 128, "lane_reduce_scatter needs 64 or 128 values");
+    __shared__ float part[4][NVAL];
+    __shared__ float logit_s[NVAL];
     const int lane = threadIdx.x & 63;
-    const int wave = blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int t0 = wave * SMALL_TOK;
-    if (t0 >= T) return;
-    float acc[SMALL_TOK][EP];
+    const int wave = threadIdx.x >> 6;
+    const int t0 = blockIdx.x * TOK;
+    float acc[NVAL];   // [token slot a][expert e] at a*EP + e
 #pragma unroll
-    for (int a = 0; a < SMALL_TOK; ++a)
+    for (int i = 0; i < NVAL; ++i) acc[i] = 0.f;
+    for (int h0 = threadIdx.x * 8; h0 < H; h0 += 2048) {
+        uint4 xv[TOK];
 #pragma unroll
-        for (int e = 0; e < EP; ++e) acc[a][e] = 0.f;
-    for (int h0 = lane * 8; h0 < H; h0 += 512) {
-        uint4 xv[SMALL_TOK];
-#pragma unroll
-        for (int a = 0; a < SMALL_TOK; ++a) {
+        for (int a = 0; a < TOK; ++a) {
             const int t = min(t0 + a, T - 1);
             xv[a] = *reinterpret_cast<const uint4*>(x + (size_t)t * H + h0);
         }
 #pragma unroll
         for (int hh = 0; hh < 8; ++hh) {
-            float xa[SMALL_TOK];
+            float xa[TOK];
 #pragma unroll
-            for (int a = 0; a < SMALL_TOK; ++a) {
+            for (int a = 0; a < TOK; ++a) {
                 const uint32_t u = (&xv[a].x)[hh >> 1];
                 xa[a] = (hh & 1) ? __uint_as_float(u & 0xffff0000u) : __uint_as_float(u << 16);
             }
@@ -142,19 +162,23 @@ __global__ __launch_bounds__(256) void route_small_kernel(const uint16_t* __rest
 #pragma unroll
             for (int e = 0; e < EP; ++e)
 #pragma unroll
-                for (int a = 0; a < SMALL_TOK; ++a) acc[a][e] = fmaf(xa[a], wv[e], acc[a][e]);
+                for (int a = 0; a < TOK; ++a) acc[a * EP + e] = fmaf(xa[a], wv[e], acc[a * EP + e]);
         }
     }
+    lane_reduce_scatter<NVAL>(acc, lane);
 #pragma unroll
-    for (int a = 0; a < SMALL_TOK; ++a) {
+    for (int i = 0; i < PER; ++i) part[wave][lane * PER + i] = acc[i];
+    __syncthreads();
+    if (threadIdx.x < NVAL) {
+        const int i = threadIdx.x;
+        logit_s[i] = ((part[0][i] + part[1][i]) + part[2][i]) + part[3][i];
+    }
+    __syncthreads();
+    for (int a = wave; a < TOK; a += 4) {
         const int t = t0 + a;
-        if (t >= T) break;  // wave-uniform
+        if (t >= T) break;  // wave-uniform; no barrier follows
         float mine = -INFINITY;
-#pragma unroll
-        for (int e = 0; e < EP; ++e) {
-            const float tot = wave_sum(acc[a][e]);
-            if (lane == e && e < E) mine = tot + (bias ? bias[e] : 0.f);
-        }
+        if (lane < E) mine = logit_s[a * EP + lane] + (bias ? bias[lane] : 0.f);
         const float v[1] = {mine};
         route_finish<1>(v, lane, t, E, k, renorm, scale, idx_out, w_out, logits_out);
     }
@@ -236,14 +260,23 @@ hipError_t launch_route_topk(const moe_shape& s, const float* partial, int split
 hipError_t launch_route(const moe_shape& s, const void* x, const void* wg, const float* bias, int32_t* idx,
                         float* w, float* logits, hipStream_t st) {
     if (s.E <= 16) {
-        const dim3 g((s.T + 4 * SMALL_TOK - 1) / (4 * SMALL_TOK)), b(256);
-#define ROUTE_SMALL(EP_, EX_)                                                                                  \
-    hipLaunchKernelGGL((route_small_kernel<EP_, EX_>), g, b, 0, st, (const uint16_t*)x, (const uint16_t*)wg, bias, \
-                       s.T, s.H, s.E, s.top_k, s.renormalize, s.routed_scale, idx, w, logits)
-        if (s.E == 8) ROUTE_SMALL(8, true);
-        else if (s.E < 8) ROUTE_SMALL(8, false);
-        else if (s.E == 16) ROUTE_SMALL(16, true);
-        else ROUTE_SMALL(16, false);
+        // Tokens per workgroup: as many as the registers hold (16 with 8 experts, 8 with 16) when
+        // that still gives every CU two workgroups, else half of that.
+        const bool big = s.T >= 2 * 256 * (s.E <= 8 ? 16 : 8);
+#define ROUTE_SMALL(EP_, EX_, TOK_)                                                                                 \
+    hipLaunchKernelGGL((route_small_kernel<EP_, EX_, TOK_>), dim3((s.T + TOK_ - 1) / TOK_), dim3(256), 0, st,          \
+                       (const uint16_t*)x, (const uint16_t*)wg, bias, s.T, s.H, s.E, s.top_k, s.renormalize,          \
+                       s.routed_scale, idx, w, logits)
+#define ROUTE_SMALL_T(EP_, EX_, TB_, TS_)      \
+    do {                                       \
+        if (big) ROUTE_SMALL(EP_, EX_, TB_);   \
+        else ROUTE_SMALL(EP_, EX_, TS_);       \
+    } while (0)
+        if (s.E == 8) ROUTE_SMALL_T(8, true, 16, 8);
+        else if (s.E < 8) ROUTE_SMALL_T(8, false, 16, 8);
+        else if (s.E == 16) ROUTE_SMALL_T(16, true, 8, 4);
+        else ROUTE_SMALL_T(16, false, 8, 4);
+#undef ROUTE_SMALL_T
 #undef ROUTE_SMALL
         return hipGetLastError();
     }
