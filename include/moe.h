@@ -113,6 +113,12 @@ size_t moe_h_scratch_bytes(const moe_shape* shape);
  *                             every short tail tile into 2 or 4 pieces run by different CUs and adds the fp32
  *                             partial sums afterwards in fixed order; 0: one piece.  Changes the summation
  *                             order of those rows only (not bit-identical between 0 and 1).
+ *   "tall_tiles"    -1|0|1|2  an expert's tail of at most 64 rows joins its last full 256-row tile (a tile of up to
+ *                             320 rows: 12-25 % more time for that tile) instead of costing a pass of its own
+ *                             over the expert's weights; 4 waves x 1 wave row only.  2: the tall tile keeps its
+ *                             place, 1: tall tiles run after the regular ones (when "tails_last"), 0: off,
+ *                             -1 (default): 2 for up to 8 tiles per expert on average, else 1.  Same results
+ *                             bit for bit.
  *   "probe_k_resident" 0 | 1  timing probe only: the GEMMs re-read their first K tile at every K step
  *                             (operands stay cache resident, RESULTS ARE MEANINGLESS); default 0
  *   "y_fp32"          0 | 1   staged calls: dtype of y_perm / y_shared: 1 (default) fp32, 0 bf16.  bf16 halves the

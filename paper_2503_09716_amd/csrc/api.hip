@@ -27,7 +27,7 @@ struct ProfRec {
 struct moe_ctx {
     int device = 0;
     char err[512] = {0};
-    GemmConfig gemm{1, 4, 0, 1, 1, 0, 0, -1, -1, 1, 0};
+    GemmConfig gemm{1, 4, 0, 1, 1, 0, 0, -1, -1, 1, 0, -1};
     bool y_fp32 = true;    // dtype of y_perm / y_shared in the staged calls
     int layer_y = -1;      // moe_layer's y_perm: 1 fp32, 0 bf16, -1 choose (its y_shared is always fp32)
     bool out_fp32 = false; // dtype of the layer output
@@ -342,9 +342,15 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     SplitTail* split_tails = (SplitTail*)(ws + L.split_tails);
     {
         StageTimer tm(c, st, MOE_STAGE_PLAN);
+        // tall tiles exist for the 4-wave, 1-wave-row kernel only
+        // In place when a group is at most one run of m-tiles (the tall tile then shares its
+        // group's W panels in L2: C2 step -4 %, against -0.5 % after the run region); after the run
+        // region for longer groups (C3: in place +5 %, after -0.7 %).
+        const double per_expert = (double)s.T * s.top_k / ((double)s.E * 256);
+        int tall = c->gemm.tall_tiles >= 0 ? c->gemm.tall_tiles : (per_expert <= 8.0 ? 2 : 1);
+        if (c->gemm.waves != 4 || c->gemm.wave_rows != 1) tall = 0;
         HIP_TRY(c, launch_ffn_plan(s, offsets, tm_up, tm_down, tl_up, tl_down, c->gemm.small_tiles != 0, ps.e_lo, ps.e_hi,
-                                   ps.shared_on, dsp, split_tails, plan,
-                                   descs_up, descs_down, st));
+                                   ps.shared_on, dsp, tall, tall, split_tails, plan, descs_up, descs_down, st));
     }
     GemmArgs a;
     memset(&a, 0, sizeof(a));
@@ -538,6 +544,7 @@ moe_status moe_set_option(moe_ctx* c, const char* key, int32_t v) {
     if (!strcmp(key, "down_tail_splits") && (v == 0 || v == 1)) { c->gemm.down_tail_splits = v; return MOE_OK; }
     if (!strcmp(key, "tails_last") && v >= -1 && v <= 1) { c->gemm.tails_last = v; return MOE_OK; }
     if (!strcmp(key, "probe_k_resident") && (v == 0 || v == 1)) { c->gemm.probe_k_resident = v; return MOE_OK; }
+    if (!strcmp(key, "tall_tiles") && v >= -1 && v <= 2) { c->gemm.tall_tiles = v; return MOE_OK; }
     if (!strcmp(key, "y_fp32") && (v == 0 || v == 1)) { c->y_fp32 = v != 0; return MOE_OK; }
     if (!strcmp(key, "layer_y_fp32") && v >= -1 && v <= 1) { c->layer_y = v; return MOE_OK; }
     if (!strcmp(key, "out_fp32") && (v == 0 || v == 1)) { c->out_fp32 = v != 0; return MOE_OK; }

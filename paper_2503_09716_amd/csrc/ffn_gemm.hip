@@ -56,7 +56,8 @@ constexpr int BK = 32;              // K elements per LDS stage
 constexpr int ROWB = BK * 2;        // bytes per LDS row
 constexpr int WROWS = 256;          // W rows per macro tile
 constexpr int NS = 4;               // LDS ring depth
-constexpr int MAX_STAGE = (256 + WROWS) * ROWB;          // 32 KiB
+constexpr int MAX_ROWS = 320;       // tallest macro tile: a full 256-row tile that also takes a short tail of its group
+constexpr int MAX_STAGE = (MAX_ROWS + WROWS) * ROWB;     // 36 KiB
 constexpr int MAX_LDS = NS * MAX_STAGE;
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
@@ -113,6 +114,12 @@ __device__ __forceinline__ void mfma_16x16x32(f32x4& c, const bf16x8& a, const b
     asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
 #endif
 }
+// The same with the accumulator in VGPRs: the X blocks of a tall tile that the 256 AGPRs do not hold.
+__device__ __forceinline__ void mfma_16x16x32_v(f32x4& c, const bf16x8& a, const bf16x8& b) {
+#if defined(__gfx950__)
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
+#endif
+}
 __device__ __forceinline__ void mfma_drain() {
 #if defined(__gfx950__)
     asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
@@ -155,7 +162,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
     constexpr int XB = 2 * TI;
     constexpr int WB = 2 * TJ;
     constexpr int WBH = WB / 2;
+    constexpr int XB_A = 64 / WB;            // X blocks whose accumulators fit the 256 AGPRs; the rest live in VGPRs
     static_assert(TJ >= 1 && (!GATED || TJ >= 2), "wave grid too wide");
+    static_assert(BM <= MAX_ROWS, "tile too tall");
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -283,8 +292,13 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
             for (int jj = 0; jj < WBH; ++jj) {
                 const int j = HF * WBH + jj;
                 const bf16x8 w = HF == 0 ? wA[jj] : wB[jj];
-                if (GATED) mfma_16x16x32(acc[j][i], w, xf[i]);
-                else mfma_16x16x32(acc[j][i], xf[i], w);
+                if (i < XB_A) {
+                    if (GATED) mfma_16x16x32(acc[j][i], w, xf[i]);
+                    else mfma_16x16x32(acc[j][i], xf[i], w);
+                } else {
+                    if (GATED) mfma_16x16x32_v(acc[j][i], w, xf[i]);
+                    else mfma_16x16x32_v(acc[j][i], xf[i], w);
+                }
             }
             if (RD) {
                 if (HF == 1) read_x(rd_stage, i);
@@ -473,13 +487,16 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_kernel(const GemmArgs p) {
     TileDesc d;
     int n_tile;
     if (!pick_tile(p, GATED, d, n_tile)) return;
-    const int blocks = p.small_tiles ? (d.nrows + 31) >> 5 : 8;  // 32-row blocks that hold real rows
+    // 32-row blocks that hold real rows; 9 or 10: a tall tile (the plan kernel makes them for this wave grid only)
+    const int blocks = d.nrows > 256 ? (d.nrows + 31) >> 5 : (p.small_tiles ? (d.nrows + 31) >> 5 : 8);
     if (WM == 2) {
         if (blocks > 4) gemm_tile<4, 2, 4, GATED>(p, d, n_tile, lds);
         else if (blocks > 2) gemm_tile<4, 2, 2, GATED>(p, d, n_tile, lds);
         else gemm_tile<4, 2, 1, GATED>(p, d, n_tile, lds);
     } else {
-        if (blocks > 4) gemm_tile<4, 1, 8, GATED>(p, d, n_tile, lds);
+        if (blocks > 9) gemm_tile<4, 1, 10, GATED>(p, d, n_tile, lds);
+        else if (blocks > 8) gemm_tile<4, 1, 9, GATED>(p, d, n_tile, lds);
+        else if (blocks > 4) gemm_tile<4, 1, 8, GATED>(p, d, n_tile, lds);
         else if (blocks > 2) gemm_tile<4, 1, 4, GATED>(p, d, n_tile, lds);
         else if (blocks > 1) gemm_tile<4, 1, 2, GATED>(p, d, n_tile, lds);
         else gemm_tile<4, 1, 1, GATED>(p, d, n_tile, lds);
@@ -519,11 +536,12 @@ __global__ __launch_bounds__(512, 2) void ffn_gemm_kernel8(const GemmArgs p) {
 __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict__ offsets, int T, int t_pad, int E, int Ns,
                                                        int tm_up, int tm_down, int tails_last_up, int tails_last_down,
                                                        int small_tiles, int e_lo, int e_hi, int shared_on, int down_splits,
+                                                       int tall_up, int tall_down,
                                                        SplitTail* __restrict__ split_tails, PlanHeader* __restrict__ plan,
                                                        TileDesc* __restrict__ descs_up, TileDesc* __restrict__ descs_down) {
     __shared__ int first[256];
     __shared__ int tail_key[256];
-    __shared__ int n_run_s;
+    __shared__ int n_run_s, n_tall_s;
     const int tid = threadIdx.x;
     // group order: g = 0 -> shared 0 (if any), then routed 0..E-1, then shared 1..Ns-1
     const int ngroups = E + Ns;
@@ -546,7 +564,12 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
         const bool mine = tid <= last;
         const bool tails_last = (which == 0 ? tails_last_up : tails_last_down) != 0;
         const int nfull = mine ? rows / tm : 0;
-        const int tail = mine ? rows - nfull * tm : 0;
+        int tail = mine ? rows - nfull * tm : 0;
+        // Tall tiles: a tail of at most 64 rows joins the group's last full 256-row tile (288 or
+        // 320 rows, 12-25 % more time for that tile) instead of costing a pass of its own over
+        // the group's weights.
+        const int joined = ((which == 0 ? tall_up : tall_down) && tm == 256 && nfull > 0 && tail <= MAX_ROWS - 256) ? tail : 0;
+        tail -= joined;
         const int blocks = (tail + 31) >> 5;   // 32-row blocks of the tail tile, 0 = none
         // A tail higher than half a tile runs the full-height variant and takes as long as a full
         // tile, so it stays with its group (keeps the group's W panels shared and the CUs in
@@ -555,22 +578,30 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
         // sums are reduced into y_perm, while shared rows belong to y_shared.)
         const bool moved = tails_last && blocks > 0 && small_tiles && blocks * 64 <= tm &&
                            !(which == 1 && down_splits > 1 && group >= E);
-        const int nrun = nfull + (blocks > 0 && !moved);   // tiles listed in group order
+        // tall_* = 2: the tall tile keeps its place in the group (it shares the W panels its
+        // neighbours stream, which is the point when a group is only a few tiles).  tall_* = 1 and
+        // tails_last: a tall tile takes longer than its neighbours and in a long launch puts the
+        // CUs it runs on out of step for the rest of it, so it leaves the group order too: tall
+        // tiles come first after the run region, one entry each, never cut along K.
+        const bool tall_moved = tails_last && joined > 0 && (which == 0 ? tall_up : tall_down) == 1;
+        const int nrun = nfull - (tall_moved ? 1 : 0) + (blocks > 0 && !moved);   // tiles listed in group order
         __syncthreads();
         first[tid] = nrun;
-        tail_key[tid] = moved ? blocks : 0;
+        tail_key[tid] = moved ? blocks : (tall_moved ? -1 : 0);
         __syncthreads();
         if (tid == 0) {
-            int run = 0, tails = 0;
+            int run = 0, tails = 0, talls = 0;
             for (int i = 0; i <= last; ++i) {
                 const int v = first[i];
                 first[i] = run;
                 run += v;
                 tails += tail_key[i] > 0;
+                talls += tail_key[i] < 0;
             }
             n_run_s = run;
+            n_tall_s = talls;
             const int per_tail = which == 1 ? down_splits : 1;   // list entries per moved tail
-            const int total = run + tails * per_tail;
+            const int total = run + talls + tails * per_tail;
             if (which == 0) { plan->n_gate_up = total; plan->n_run_up = run; }
             else { plan->n_down = total; plan->n_run_down = run; plan->n_split_tails = down_splits > 1 ? tails : 0; }
         }
@@ -580,10 +611,20 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
             d.group = group;
             d.srow = srow;
             const int base = first[tid];
+            const int nlisted = nfull - (tall_moved ? 1 : 0);   // full tiles listed in group order
             for (int i = 0; i < nrun; ++i) {
-                d.row0 = row_begin + i * tm;
-                d.nrows = min(tm, rows - i * tm);
+                // entry nlisted (if any) is a tail that stays with its group; it starts after all full tiles
+                const int at = i < nlisted ? i : nfull;
+                d.row0 = row_begin + at * tm;
+                d.nrows = min(tm, rows - at * tm) + ((at == nfull - 1 && !tall_moved) ? joined : 0);
                 descs[base + i] = d;
+            }
+            if (tall_moved) {
+                int before = 0;
+                for (int i = 0; i < tid; ++i) before += tail_key[i] < 0;
+                d.row0 = row_begin + (nfull - 1) * tm;
+                d.nrows = tm + joined;
+                descs[n_run_s + before] = d;
             }
             if (moved) {
                 int rank = 0;   // tails that come before this one
@@ -593,16 +634,17 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
                 }
                 d.row0 = row_begin + nfull * tm;
                 d.nrows = tail;
+                const int tbase = n_run_s + n_tall_s;
                 if (which == 1 && down_splits > 1) {
                     // one entry per K piece; the pieces' partial sums are added up after the launch
                     for (int sp = 0; sp < down_splits; ++sp) {
                         d.srow = -2 - (rank * down_splits + sp);
-                        descs[n_run_s + rank * down_splits + sp] = d;
+                        descs[tbase + rank * down_splits + sp] = d;
                     }
                     split_tails[rank].row0 = d.row0;
                     split_tails[rank].nrows = tail;
                 } else {
-                    descs[n_run_s + rank] = d;
+                    descs[tbase + rank] = d;
                 }
             }
         }
@@ -666,11 +708,11 @@ hipError_t ffn_gemm_init() {
 
 hipError_t launch_ffn_plan(const moe_shape& s, const int32_t* offsets, int tm_up, int tm_down, bool tails_last_up,
                            bool tails_last_down, bool small_tiles, int e_lo, int e_hi, bool shared_on,
-                           int down_tail_splits, SplitTail* split_tails, PlanHeader* plan, TileDesc* descs_up,
-                           TileDesc* descs_down, hipStream_t st) {
+                           int down_tail_splits, int tall_up, int tall_down, SplitTail* split_tails, PlanHeader* plan,
+                           TileDesc* descs_up, TileDesc* descs_down, hipStream_t st) {
     hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(256), 0, st, offsets, s.T, (s.T + 15) & ~15, s.E, s.num_shared, tm_up, tm_down,
                        tails_last_up ? 1 : 0, tails_last_down ? 1 : 0, small_tiles ? 1 : 0, e_lo, e_hi, shared_on ? 1 : 0,
-                       tails_last_down ? down_tail_splits : 1, split_tails, plan, descs_up, descs_down);
+                       tails_last_down ? down_tail_splits : 1, tall_up, tall_down, split_tails, plan, descs_up, descs_down);
     return hipGetLastError();
 }
 

@@ -135,7 +135,8 @@ def test_tile_order_options_give_same_bits(moe):
 
 def check_tile_orders(moe, gl):
     ref = gl.run_layer(True)
-    for key, default, values in (("tails_last", -1, (0, 1)), ("gemm_group_m", 0, (1, 3, 16)), ("xcd_remap", 1, (0,))):
+    for key, default, values in (("tails_last", -1, (0, 1)), ("gemm_group_m", 0, (1, 3, 16)), ("xcd_remap", 1, (0,)),
+                                 ("tall_tiles", -1, (0, 1, 2))):
         for v in values:
             moe.set_option(key, v)
             try:
@@ -343,7 +344,7 @@ def test_layer_random_k_split_shapes(moe, seed):
 
 
 OPTION_DEFAULTS = {"tails_last": -1, "gemm_group_m": 0, "xcd_remap": 1, "x_tiled": -1, "small_tiles": 1,
-                   "gemm_tile_rows_up": 0, "gemm_tile_rows_down": 0, "gemm_waves": 4, "gemm_wave_rows": 1}
+                   "gemm_tile_rows_up": 0, "gemm_tile_rows_down": 0, "gemm_waves": 4, "gemm_wave_rows": 1, "tall_tiles": -1}
 
 
 @pytest.mark.parametrize("seed", range(48))
@@ -374,7 +375,8 @@ def test_layer_fuzz_entry_points_and_options(moe, seed):
     got = torch.full_like(out, float("nan"))
     opts = {k: int(rng.choice(v)) for k, v in (
         ("tails_last", (0, 1)), ("gemm_group_m", (0, 1, 5, 16)), ("xcd_remap", (0, 1)), ("x_tiled", (0, 1)),
-        ("small_tiles", (0, 1)), ("gemm_tile_rows_up", (0, 128, 256)), ("gemm_tile_rows_down", (0, 128, 256)))}
+        ("small_tiles", (0, 1)), ("gemm_tile_rows_up", (0, 128, 256)), ("gemm_tile_rows_down", (0, 128, 256)),
+        ("tall_tiles", (0, 1, 2)))}
     opts["gemm_waves"], opts["gemm_wave_rows"] = [(4, 1), (4, 2), (8, 2), (8, 4)][int(rng.integers(0, 4))]
     be = int(rng.integers(1, cfg.T + 1))
     say("streamed", per_group, num_slots, "options", opts, "tokens per pass", be)
