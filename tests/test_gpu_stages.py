@@ -217,6 +217,41 @@ def test_grouped_ffn(moe, name, over, skew, waves, wave_rows, small_tiles, row_t
         say(P.assert_output(ysh.float().cpu().numpy(), ref_s, "y_shared"))
 
 
+TAIL_COUNTS = [256 + 1, 256 + 32, 256 + 33, 256 + 64, 256 + 65, 512 + 40, 255, 1, 0, 300, 256, 768 + 64, 129, 64]
+
+
+@pytest.mark.parametrize("F,num_shared,tall", [(128, 0, -1), (128, 2, -1), (512, 0, -1), (512, 1, -1), (512, 1, 1), (128, 2, 0)])
+def test_grouped_ffn_every_tail_class(moe, F, num_shared, tall):
+    """Prescribed rows per expert (top-1 routing laid out by hand) so that one launch holds every
+    kind of m-tile: tails of 1, 32, 33 and 64 rows that join a full tile (288- and 320-row tiles),
+    a 65-row tail that does not, short tails that are moved (and cut along K when F = 512), tails
+    above half a tile, an empty expert, single-row and exact-multiple groups; T itself ends in a
+    short tail for the shared experts.  Every row against the oracle."""
+    counts = np.array(TAIL_COUNTS)
+    E, T = len(counts), int(counts.sum())
+    cfg = scaled_config("C4", T=T, H=192, F=F, E=E, top_k=1, num_shared=num_shared)
+    idx_h = np.repeat(np.arange(E, dtype=np.int32), counts)
+    idx_h = idx_h[np.random.default_rng(5).permutation(T)].reshape(T, 1)
+    say("tail classes", cfg, "tall_tiles", tall)
+    moe.set_option("tall_tiles", tall)
+    try:
+        y, ysh, perm, off, li = run_ffn_stage(moe, cfg, idx_h, wave_rows=1)
+    finally:
+        moe.set_option("tall_tiles", -1)
+    np.testing.assert_array_equal(np.diff(off), counts)
+    u = torch_bf16_to_u16
+    hw1 = [u(t) for t in li.w1]; hw3 = [u(t) for t in li.w3]; hw2 = [u(t) for t in li.w2]
+    hx = u(li.x)
+    eid = np.repeat(np.arange(E, dtype=np.int32), counts)
+    ref = orc.expert_rows(hx[perm], eid, hw1, hw3, hw2)
+    say(P.assert_output(y.float().cpu().numpy(), ref, "y_perm"))
+    if num_shared:
+        ref_s = np.zeros((T, cfg.H), np.float32)
+        for sh in range(num_shared):
+            ref_s += orc.expert_rows(hx, np.full(T, E + sh, np.int32), hw1, hw3, hw2)
+        say(P.assert_output(ysh.float().cpu().numpy(), ref_s, "y_shared"))
+
+
 def test_grouped_ffn_bf16_y(moe):
     """Option y_fp32 = 0: y in bf16 is the RNE rounding of the fp32 y, bit for bit."""
     cfg = scaled_config("C4", T=300, H=256, F=192, E=16, top_k=4)
