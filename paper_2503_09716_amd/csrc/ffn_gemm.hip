@@ -342,10 +342,20 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
         }
         if (KT >= NS - 1) ring_sync<(NS - 2) * NL>();
         else ring_sync<0>();
+        // Same order as the reads inside the loop (the first-half W blocks among the first X
+        // blocks): LDS reads return in order, and where the two paths into the loop meet the
+        // compiler waits for whichever leaves fewer reads outstanding behind the registers the
+        // first MFMAs need.  With the W blocks read last here (where the scheduler puts them if
+        // left alone), that was a wait for every read of the previous iteration at the top of
+        // each sub-tile.
+        constexpr int RPGW0 = (WBH + XB - 1) / XB;
 #pragma unroll
-        for (int i = 0; i < XB; ++i) read_x(0, i);
+        for (int i = 0; i < XB; ++i) {
+            read_x(0, i);
 #pragma unroll
-        for (int jj = 0; jj < WBH; ++jj) read_w(0, 0, jj);
+            for (int jj = i * RPGW0; jj < (i + 1) * RPGW0 && jj < WBH; ++jj) read_w(0, 0, jj);
+            __builtin_amdgcn_sched_barrier(0);   // keeps the compiler from moving the W reads to the end
+        }
 
         using H0 = std::integral_constant<int, 0>;
         using H1 = std::integral_constant<int, 1>;
