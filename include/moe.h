@@ -101,8 +101,9 @@ size_t moe_h_scratch_bytes(const moe_shape* shape);
  *                             the typical number of tiles per expert, between 4 and 8
  *   "xcd_remap"       0 | 1   give each XCD runs of consecutive tiles
  *   "small_tiles"     0 | 1   use 128/64/32-row tiles for the ragged tail of an expert
- *   "gemm_tile_rows_up" / "gemm_tile_rows_down"  0 | 128 | 256   rows per m-tile of the gate/up and
- *                             the down GEMM; 0 (default) picks per launch from the tile count
+ *   "gemm_tile_rows_up" / "gemm_tile_rows_down"  0 | 128 | 256 | 320   rows per m-tile of the gate/up and
+ *                             the down GEMM; 0 (default) picks per launch from the tile count and the mean
+ *                             rows per expert (320: 4 waves x 1 wave row only, else treated as 256)
  *   "x_tiled"         -1|0|1  moe_layer: 1 gathers x once into a block-tiled x_perm that the gate/up GEMM
  *                             loads in 1 KiB pieces, 0 fuses the gather into that GEMM's loads, -1 (default)
  *                             chooses by expert width.  Same results bit for bit.

@@ -330,8 +330,18 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     TileDesc* descs_down = (TileDesc*)(ws + L.descs_down);
     const size_t Rpad = ((size_t)s.T * s.top_k + 15) & ~(size_t)15;   // shared experts' rows of h start block-aligned
     const int nt_up = (s.F + 127) / 128, nt_down = (s.H + 255) / 256;
-    const int tm_up = c->gemm.tile_rows_up ? c->gemm.tile_rows_up : pick_tile_rows(s, nt_up, s.num_shared);
-    const int tm_down = c->gemm.tile_rows_down ? c->gemm.tile_rows_down : pick_tile_rows(s, nt_down, s.num_shared ? 1 : 0);
+    int tm_up = c->gemm.tile_rows_up ? c->gemm.tile_rows_up : pick_tile_rows(s, nt_up, s.num_shared);
+    int tm_down = c->gemm.tile_rows_down ? c->gemm.tile_rows_down : pick_tile_rows(s, nt_down, s.num_shared ? 1 : 0);
+    // tiles above 256 rows exist for the 4-wave, 1-wave-row kernel only
+    const bool tall_kernel = c->gemm.waves == 4 && c->gemm.wave_rows == 1;
+    // Gate/up GEMM: 320-row tiles move 10 % fewer bytes per FLOP from L2 to LDS (the chip is
+    // power-limited, and what the loads cost is clock), measured -1.3 % (C3) to -3.9 % (C4, C5) on
+    // that GEMM; not when an expert is only about four tiles (C2: 1024 rows = 3 tiles + a tail
+    // that needs a pass of its own, +10 %).  The down GEMM's 320-row variant is slower than its
+    // 256-row one (C4/C5 +18 %), so it keeps 256.
+    if (!c->gemm.tile_rows_up && tall_kernel && tm_up == 256 && (double)s.T * s.top_k / s.E >= 1200.0) tm_up = 320;
+    if (!tall_kernel && tm_up > 256) tm_up = 256;
+    if (!tall_kernel && tm_down > 256) tm_down = 256;
     // Short tail tiles go last by default: the other tiles of a launch then all take the same
     // time, which keeps the CUs that share operand panels in L2 in step (measured: the L2 miss
     // traffic of the gate/up GEMM doubles when short tiles are mixed in), and the launch ends on
@@ -348,7 +358,7 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
         // region for longer groups (C3: in place +5 %, after -0.7 %).
         const double per_expert = (double)s.T * s.top_k / ((double)s.E * 256);
         int tall = c->gemm.tall_tiles >= 0 ? c->gemm.tall_tiles : (per_expert <= 8.0 ? 2 : 1);
-        if (c->gemm.waves != 4 || c->gemm.wave_rows != 1) tall = 0;
+        if (!tall_kernel) tall = 0;
         HIP_TRY(c, launch_ffn_plan(s, offsets, tm_up, tm_down, tl_up, tl_down, c->gemm.small_tiles != 0, ps.e_lo, ps.e_hi,
                                    ps.shared_on, dsp, tall, tall, split_tails, plan, descs_up, descs_down, st));
     }
@@ -538,8 +548,8 @@ moe_status moe_set_option(moe_ctx* c, const char* key, int32_t v) {
     if (!strcmp(key, "gemm_group_m") && v >= 0 && v <= 64) { c->gemm.group_m = v; return MOE_OK; }
     if (!strcmp(key, "xcd_remap") && (v == 0 || v == 1)) { c->gemm.xcd_remap = v; return MOE_OK; }
     if (!strcmp(key, "small_tiles") && (v == 0 || v == 1)) { c->gemm.small_tiles = v; return MOE_OK; }
-    if (!strcmp(key, "gemm_tile_rows_up") && (v == 0 || v == 128 || v == 256)) { c->gemm.tile_rows_up = v; return MOE_OK; }
-    if (!strcmp(key, "gemm_tile_rows_down") && (v == 0 || v == 128 || v == 256)) { c->gemm.tile_rows_down = v; return MOE_OK; }
+    if (!strcmp(key, "gemm_tile_rows_up") && (v == 0 || v == 128 || v == 256 || v == 320)) { c->gemm.tile_rows_up = v; return MOE_OK; }
+    if (!strcmp(key, "gemm_tile_rows_down") && (v == 0 || v == 128 || v == 256 || v == 320)) { c->gemm.tile_rows_down = v; return MOE_OK; }
     if (!strcmp(key, "x_tiled") && v >= -1 && v <= 1) { c->gemm.x_tiled = v; return MOE_OK; }
     if (!strcmp(key, "down_tail_splits") && (v == 0 || v == 1)) { c->gemm.down_tail_splits = v; return MOE_OK; }
     if (!strcmp(key, "tails_last") && v >= -1 && v <= 1) { c->gemm.tails_last = v; return MOE_OK; }

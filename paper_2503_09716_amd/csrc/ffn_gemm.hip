@@ -586,7 +586,8 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
         // step); only a short tail is moved to the end of the list.
         // (A shared expert's tail is not moved in a down list with K pieces: the pieces' partial
         // sums are reduced into y_perm, while shared rows belong to y_shared.)
-        const bool moved = tails_last && blocks > 0 && small_tiles && blocks * 64 <= tm &&
+        // (at most 128 rows: the K pieces' partial buffers hold SPLIT_TAIL_ROWS rows)
+        const bool moved = tails_last && blocks > 0 && small_tiles && blocks * 64 <= min(tm, 2 * SPLIT_TAIL_ROWS) &&
                            !(which == 1 && down_splits > 1 && group >= E);
         // tall_* = 2: the tall tile keeps its place in the group (it shares the W panels its
         // neighbours stream, which is the point when a group is only a few tiles).  tall_* = 1 and

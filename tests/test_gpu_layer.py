@@ -375,7 +375,7 @@ def test_layer_fuzz_entry_points_and_options(moe, seed):
     got = torch.full_like(out, float("nan"))
     opts = {k: int(rng.choice(v)) for k, v in (
         ("tails_last", (0, 1)), ("gemm_group_m", (0, 1, 5, 16)), ("xcd_remap", (0, 1)), ("x_tiled", (0, 1)),
-        ("small_tiles", (0, 1)), ("gemm_tile_rows_up", (0, 128, 256)), ("gemm_tile_rows_down", (0, 128, 256)),
+        ("small_tiles", (0, 1)), ("gemm_tile_rows_up", (0, 128, 256, 320)), ("gemm_tile_rows_down", (0, 128, 256, 320)),
         ("tall_tiles", (0, 1, 2)))}
     opts["gemm_waves"], opts["gemm_wave_rows"] = [(4, 1), (4, 2), (8, 2), (8, 4)][int(rng.integers(0, 4))]
     be = int(rng.integers(1, cfg.T + 1))
