@@ -337,8 +337,8 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     // Gate/up GEMM: 320-row tiles move 10 % fewer bytes per FLOP from L2 to LDS (the chip is
     // power-limited, and what the loads cost is clock), measured -1.3 % (C3) to -3.9 % (C4, C5) on
     // that GEMM; not when an expert is only about four tiles (C2: 1024 rows = 3 tiles + a tail
-    // that needs a pass of its own, +10 %).  The down GEMM's 320-row variant is slower than its
-    // 256-row one (C4/C5 +18 %), so it keeps 256.
+    // that needs a pass of its own, +10 %).  In the down GEMM the 320-row variant measures within
+    // 1 % of the 256-row one either way, so it keeps 256.
     if (!c->gemm.tile_rows_up && tall_kernel && tm_up == 256 && (double)s.T * s.top_k / s.E >= 1200.0) tm_up = 320;
     if (!tall_kernel && tm_up > 256) tm_up = 256;
     if (!tall_kernel && tm_down > 256) tm_down = 256;

@@ -423,23 +423,43 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
         // block j and the 4 consecutive rows 4*(lane/16) .. +3 of X block i.  One store
         // instruction writes 4 rows x 64 contiguous bytes (fp32).  Rows past the end of the
         // group and columns past N fall outside the buffer descriptor, which spans exactly the
-        // tile's valid rows, and are dropped by hardware.
+        // valid rows of the 16-row block being stored, and are dropped by hardware.
+        // The descriptor is rebuilt (scalar work) for every 16-row block of X so that the row
+        // part of the address is in its base and the 16 per-lane offsets {W block j, row r} are
+        // computed once per tile: a store then needs no vector address arithmetic and no
+        // registers beyond its data.
         auto store_tile = [&](auto f32_tag) __attribute__((always_inline)) {
             constexpr bool F32 = decltype(f32_tag)::value;
             constexpr int esz = F32 ? 4 : 2;
             const uint32_t rowbytes = (uint32_t)N * (uint32_t)esz;
-            const __amdgpu_buffer_rsrc_t rs_o = tile_rsrc(out + (size_t)orow_base * rowbytes, (uint32_t)d.nrows * rowbytes);
+            uint32_t vcol[WB][4];
+#pragma unroll
+            for (int j = 0; j < WB; ++j) {
+                const int col = n0 + bw0 * 32 + j * 16 + rl;
+                const uint32_t base = col < N ? (uint32_t)(g * 4) * rowbytes + (uint32_t)col * esz : 0x80000000u;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) vcol[j][r] = base + (uint32_t)r * rowbytes;
+            }
 #pragma unroll
             for (int i = 0; i < XB; ++i) {
+                const int r0 = bx0 * 32 + i * 16;                          // wave-uniform
+                const int left = min(max(d.nrows - r0, 0), 16);            // valid rows of this block
+                const __amdgpu_buffer_rsrc_t rs_o =
+                    tile_rsrc(out + (size_t)(orow_base + r0) * rowbytes, (uint32_t)left * rowbytes);
 #pragma unroll
                 for (int j = 0; j < WB; ++j) {
-                    const int col = n0 + bw0 * 32 + j * 16 + rl;
-                    const uint32_t row = (uint32_t)(bx0 * 32 + i * 16 + g * 4);
-                    const uint32_t voff = col < N ? row * rowbytes + (uint32_t)col * esz : 0x80000000u;
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        if (F32) buffer_store_b32(rs_o, voff + (uint32_t)r * rowbytes, acc[j][i][r]);
-                        else buffer_store_bf16(rs_o, voff + (uint32_t)r * rowbytes, acc[j][i][r]);
+                        if (F32) {
+                            buffer_store_b32(rs_o, vcol[j][r], acc[j][i][r]);
+                        } else {
+                            // read the accumulator here, not earlier: left alone the compiler copies all
+                            // accumulators to VGPRs ahead of the first store and spills to make room
+                            float v;
+                            if (i < XB_A) asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(acc[j][i][r]) : "memory");
+                            else asm volatile("v_mov_b32 %0, %1" : "=v"(v) : "v"(acc[j][i][r]) : "memory");
+                            buffer_store_bf16(rs_o, vcol[j][r], v);
+                        }
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);   // one block row at a time
