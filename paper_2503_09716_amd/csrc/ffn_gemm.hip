@@ -15,9 +15,12 @@
 // unless a tiled copy exists.
 //
 // Tile routine (one workgroup = NW wavefronts in a WM x WN grid):
-//   * macro tile: BM rows of X (256/128/64/32) x 256 rows of W (GEMM 1: 128 gate + 128 up rows,
-//     so the SiLU-gate product is formed in registers); K advances in sub-tiles of 32.
-//   * global -> LDS with global_load_lds_dwordx4 (no VGPR round trip) into a ring of NS = 4
+//   * macro tile: BM rows of X (320/288/256/128/64/32) x 256 rows of W (GEMM 1: 128 gate + 128
+//     up rows, so the SiLU-gate product is formed in registers); K advances in sub-tiles of 32.
+//     The 288- and 320-row tiles (4 waves side by side only) keep the accumulators of their last
+//     2-4 X blocks in VGPRs, the 256 AGPRs being full; they serve as the standard tile of GEMM 1
+//     for large experts (fewer bytes from L2 per FLOP) and take in an expert's short tail.
+//   * global -> LDS with buffer_load_dwordx4 ... lds (no VGPR round trip) into a ring of NS = 4
 //     LDS stages (4 x 32 KiB at BM = 256): the loads of sub-tile t+3 are issued while sub-tile t
 //     is multiplied, so HBM latency has three sub-tiles of MFMA work to hide behind, and they
 //     are spread between the MFMAs (one every few) instead of bursting after the barrier.
