@@ -10,19 +10,52 @@
 //             route_topk_kernel then sums the partials, adds the bias and selects.
 // Selection: 64 lanes hold a token's logits, max / sum are butterfly reductions and top-k is k
 // rounds of a wave-wide arg-max on the logits (ties resolved towards the lower expert id).
+#include <type_traits>
+
 #include "common.h"
 
 namespace moe {
 namespace {
 
+// Butterfly step M of a wave-wide reduction: the value held by this lane's partner, the lane
+// that differs from it in bit log2(M) and agrees in all higher bits.  Inside a row of 16 lanes
+// the partner comes through the VALU's data-parallel-primitive path (quad permutes for M = 1, 2;
+// half-row and row mirrors for M = 4, 8: lane i with 7-i, 15-i, which also flip the lower bits,
+// and any partner with the same higher bits will do for a reduction); only M = 16, 32 go
+// through the LDS crossbar, whose throughput per CU is what bounded the top-k kernels.
+template <int CTRL>
+__device__ __forceinline__ int dpp_move(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, false);
+}
+template <int M>
+__device__ __forceinline__ int pair_i(int v) {
+    if constexpr (M == 1) return dpp_move<0xB1>(v);        // quad_perm [1,0,3,2]
+    else if constexpr (M == 2) return dpp_move<0x4E>(v);   // quad_perm [2,3,0,1]
+    else if constexpr (M == 4) return dpp_move<0x141>(v);  // row_half_mirror
+    else if constexpr (M == 8) return dpp_move<0x140>(v);  // row_mirror
+    else return __shfl_xor(v, M, 64);
+}
+template <int M>
+__device__ __forceinline__ float pair_f(float v) {
+    return __int_as_float(pair_i<M>(__float_as_int(v)));
+}
+
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
+    v = fmaxf(v, pair_f<1>(v));
+    v = fmaxf(v, pair_f<2>(v));
+    v = fmaxf(v, pair_f<4>(v));
+    v = fmaxf(v, pair_f<8>(v));
+    v = fmaxf(v, pair_f<16>(v));
+    v = fmaxf(v, pair_f<32>(v));
     return v;
 }
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+    v += pair_f<1>(v);
+    v += pair_f<2>(v);
+    v += pair_f<4>(v);
+    v += pair_f<8>(v);
+    v += pair_f<16>(v);
+    v += pair_f<32>(v);
     return v;
 }
 
@@ -64,14 +97,21 @@ __device__ __forceinline__ void route_finish(const float (&v)[NV], const int lan
             const bool ok = e < E && !((taken >> i) & 1u);
             if (ok && (be == 0x7fffffff || v[i] > bv)) { bv = v[i]; be = e; bp = p[i]; }
         }
-        // wave arg-max, ties -> lower expert id
-#pragma unroll
-        for (int s = 32; s >= 1; s >>= 1) {
-            const float ov = __shfl_xor(bv, s, 64);
-            const int oe = __shfl_xor(be, s, 64);
-            const float op = __shfl_xor(bp, s, 64);
+        // wave arg-max, ties -> lower expert id ((value, -id) is a total order, so the result does
+        // not depend on how the lanes are paired)
+        auto step = [&](auto m_tag) __attribute__((always_inline)) {
+            constexpr int M = decltype(m_tag)::value;
+            const float ov = pair_f<M>(bv);
+            const int oe = pair_i<M>(be);
+            const float op = pair_f<M>(bp);
             if (ov > bv || (ov == bv && oe < be)) { bv = ov; be = oe; bp = op; }
-        }
+        };
+        step(std::integral_constant<int, 1>{});
+        step(std::integral_constant<int, 2>{});
+        step(std::integral_constant<int, 4>{});
+        step(std::integral_constant<int, 8>{});
+        step(std::integral_constant<int, 16>{});
+        step(std::integral_constant<int, 32>{});
         if (lane == j) { my_e = be; my_w = bp * rz; }
         // retire the winner
 #pragma unroll
@@ -99,7 +139,7 @@ __device__ __forceinline__ void lane_reduce_scatter(float (&v)[N], const int lan
     for (int i = 0; i < HALF; ++i) {
         const float keep = up ? v[i + HALF] : v[i];
         const float send = up ? v[i] : v[i + HALF];
-        v[i] = keep + __shfl_xor(send, MASK, 64);
+        v[i] = keep + pair_f<MASK>(send);
     }
     if constexpr (MASK > 1) lane_reduce_scatter<N, HALF / 2, MASK / 2>(v, lane);
 }
