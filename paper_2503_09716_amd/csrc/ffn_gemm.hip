@@ -555,6 +555,31 @@ __global__ __launch_bounds__(512, 2) void ffn_gemm_kernel8(const GemmArgs p) {
     }
 }
 
+// Exclusive prefix sums of three per-thread counters over the 256 threads of a workgroup, and
+// their totals (every thread gets them): a wave-level scan, then the four wave sums through LDS.
+__device__ __forceinline__ void block_scan3(int& a, int& b, int& c, int (&tot)[3], int (*wsum)[3], const int tid) {
+    const int lane = tid & 63, w = tid >> 6;
+    int ia = a, ib = b, ic = c;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int ta = __shfl_up(ia, d, 64), tb = __shfl_up(ib, d, 64), tc = __shfl_up(ic, d, 64);
+        if (lane >= d) { ia += ta; ib += tb; ic += tc; }
+    }
+    if (lane == 63) { wsum[w][0] = ia; wsum[w][1] = ib; wsum[w][2] = ic; }
+    __syncthreads();
+    int oa = 0, ob = 0, oc = 0;
+    tot[0] = tot[1] = tot[2] = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (i < w) { oa += wsum[i][0]; ob += wsum[i][1]; oc += wsum[i][2]; }
+        tot[0] += wsum[i][0]; tot[1] += wsum[i][1]; tot[2] += wsum[i][2];
+    }
+    __syncthreads();   // wsum may be written again
+    a = oa + ia - a;
+    b = ob + ib - b;
+    c = oc + ic - c;
+}
+
 // Builds the two m-tile lists (gate/up GEMM with tiles of tm_up rows, down GEMM with tm_down rows)
 // from expert_offsets.  Group order: shared expert 0, routed experts, shared experts 1.. (the down
 // GEMM takes the first two parts only: shared experts are concatenated along K there).
@@ -572,9 +597,7 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
                                                        int tall_up, int tall_down,
                                                        SplitTail* __restrict__ split_tails, PlanHeader* __restrict__ plan,
                                                        TileDesc* __restrict__ descs_up, TileDesc* __restrict__ descs_down) {
-    __shared__ int first[256];
-    __shared__ int tail_key[256];
-    __shared__ int n_run_s, n_tall_s;
+    __shared__ int wsum[4][3];
     const int tid = threadIdx.x;
     // group order: g = 0 -> shared 0 (if any), then routed 0..E-1, then shared 1..Ns-1
     const int ngroups = E + Ns;
@@ -619,32 +642,28 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
         // tiles come first after the run region, one entry each, never cut along K.
         const bool tall_moved = tails_last && joined > 0 && (which == 0 ? tall_up : tall_down) == 1;
         const int nrun = nfull - (tall_moved ? 1 : 0) + (blocks > 0 && !moved);   // tiles listed in group order
-        __syncthreads();
-        first[tid] = nrun;
-        tail_key[tid] = moved ? blocks : (tall_moved ? -1 : 0);
-        __syncthreads();
+        // Positions by prefix sums over the groups (at most 256, one per thread): tiles listed in
+        // group order; tall tiles moved behind them; moved short tails, counted per height in
+        // 32-row blocks (1..4), three 10-bit counters to a word.
+        int base = nrun;
+        int k2 = (tall_moved ? 1 : 0) | (moved && blocks == 1 ? 1 << 10 : 0) | (moved && blocks == 2 ? 1 << 20 : 0);
+        int k3 = (moved && blocks == 3 ? 1 : 0) | (moved && blocks == 4 ? 1 << 10 : 0);
+        int tot[3];
+        block_scan3(base, k2, k3, tot, wsum, tid);
+        const int n_run_s = tot[0], n_tall_s = tot[1] & 1023;
+        const int cnt[5] = {0, (tot[1] >> 10) & 1023, (tot[1] >> 20) & 1023, tot[2] & 1023, (tot[2] >> 10) & 1023};
+        const int pre[5] = {0, (k2 >> 10) & 1023, (k2 >> 20) & 1023, k3 & 1023, (k3 >> 10) & 1023};
+        const int tails = cnt[1] + cnt[2] + cnt[3] + cnt[4];
         if (tid == 0) {
-            int run = 0, tails = 0, talls = 0;
-            for (int i = 0; i <= last; ++i) {
-                const int v = first[i];
-                first[i] = run;
-                run += v;
-                tails += tail_key[i] > 0;
-                talls += tail_key[i] < 0;
-            }
-            n_run_s = run;
-            n_tall_s = talls;
             const int per_tail = which == 1 ? down_splits : 1;   // list entries per moved tail
-            const int total = run + talls + tails * per_tail;
-            if (which == 0) { plan->n_gate_up = total; plan->n_run_up = run; }
-            else { plan->n_down = total; plan->n_run_down = run; plan->n_split_tails = down_splits > 1 ? tails : 0; }
+            const int total = n_run_s + n_tall_s + tails * per_tail;
+            if (which == 0) { plan->n_gate_up = total; plan->n_run_up = n_run_s; }
+            else { plan->n_down = total; plan->n_run_down = n_run_s; plan->n_split_tails = down_splits > 1 ? tails : 0; }
         }
-        __syncthreads();
         if (mine) {
             TileDesc d;
             d.group = group;
             d.srow = srow;
-            const int base = first[tid];
             const int nlisted = nfull - (tall_moved ? 1 : 0);   // full tiles listed in group order
             for (int i = 0; i < nrun; ++i) {
                 // entry nlisted (if any) is a tail that stays with its group; it starts after all full tiles
@@ -654,18 +673,15 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
                 descs[base + i] = d;
             }
             if (tall_moved) {
-                int before = 0;
-                for (int i = 0; i < tid; ++i) before += tail_key[i] < 0;
+                const int before = k2 & 1023;   // tall tiles of the groups before this one
                 d.row0 = row_begin + (nfull - 1) * tm;
                 d.nrows = tm + joined;
                 descs[n_run_s + before] = d;
             }
             if (moved) {
-                int rank = 0;   // tails that come before this one
-                for (int i = 0; i <= last; ++i) {
-                    const int b = tail_key[i];
-                    rank += (b > blocks) || (b == blocks && i < tid);
-                }
+                // tails that come before this one: the higher ones, and those as high of earlier groups
+                int rank = pre[blocks];
+                for (int b = blocks + 1; b <= 4; ++b) rank += cnt[b];
                 d.row0 = row_begin + nfull * tm;
                 d.nrows = tail;
                 const int tbase = n_run_s + n_tall_s;
