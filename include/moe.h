@@ -32,6 +32,8 @@
  *    Weights are static, so packing is not part of the timed path.
  *  - Limits: H % 64 == 0, F % 64 == 0, 1 <= top_k <= E <= 256, top_k <= 64,
  *    0 <= num_shared <= 8, every matrix below 4 GiB.  Other shapes: MOE_E_UNSUPPORTED.
+ *  - An empty batch (T = 0) is valid: the call returns MOE_OK, reads no buffer and enqueues
+ *    nothing, except that moe_permute writes expert_offsets = 0 (every group is empty).
  */
 #ifndef MOE_MI355_H
 #define MOE_MI355_H

@@ -74,7 +74,7 @@ moe_status fail(moe_ctx* c, moe_status st, const char* fmt, ...) {
 const char* shape_problem(const moe_shape* s, moe_status* st) {
     *st = MOE_E_ARG;
     if (!s) return "shape is NULL";
-    if (s->T < 1 || s->H < 1 || s->F < 1 || s->E < 1 || s->top_k < 1) return "T, H, F, E, top_k must be >= 1";
+    if (s->T < 0 || s->H < 1 || s->F < 1 || s->E < 1 || s->top_k < 1) return "T must be >= 0; H, F, E, top_k >= 1";
     if (s->top_k > s->E) return "top_k > E";
     if (s->num_shared < 0) return "num_shared < 0";
     if (s->renormalize != 0 && s->renormalize != 1) return "renormalize must be 0 or 1";
@@ -575,6 +575,7 @@ moe_status moe_pack_weight(moe_ctx* c, const void* w, int32_t rows, int32_t cols
 moe_status moe_route(moe_ctx* c, const moe_shape* s, const void* x, const void* wg, const float* bias,
                      int32_t* idx, float* w, float* logits, void* ws, size_t ws_bytes, void* stream) {
     if (moe_status st = check_common(c, s)) return st;
+    if (s->T == 0) return MOE_OK;   // an empty batch: nothing to do
     if (!x || !wg || !idx || !w) return fail(c, MOE_E_ARG, "route: NULL pointer");
     if (moe_status st = check_ws(c, s, ws, ws_bytes)) return st;
     hipStream_t hs = (hipStream_t)stream;
@@ -586,6 +587,11 @@ moe_status moe_permute(moe_ctx* c, const moe_shape* s, const void* x, const int3
                        int32_t* offsets, int32_t* perm, int32_t* inv_perm, int32_t* row_token, void* ws,
                        size_t ws_bytes, void* stream) {
     if (moe_status st = check_common(c, s)) return st;
+    if (s->T == 0) {   // an empty batch: every group is empty
+        if (!offsets) return fail(c, MOE_E_ARG, "permute: NULL pointer");
+        HIP_TRY(c, launch_zero_offsets(s->E, offsets, (hipStream_t)stream));
+        return MOE_OK;
+    }
     if (!idx || !offsets || !perm || !inv_perm) return fail(c, MOE_E_ARG, "permute: NULL pointer");
     if (x_perm && !x) return fail(c, MOE_E_ARG, "permute: x is NULL but x_perm was requested");
     if (moe_status st = check_ws(c, s, ws, ws_bytes)) return st;
@@ -608,6 +614,7 @@ moe_status moe_grouped_ffn(moe_ctx* c, const moe_shape* s, const void* x_perm, c
                            const void* const* w2p, void* h, void* y_perm, void* y_shared, void* ws, size_t ws_bytes,
                            void* stream) {
     if (moe_status st = check_common(c, s)) return st;
+    if (s->T == 0) return MOE_OK;   // an empty batch: nothing to do
     if (!offsets || !h || !y_perm) return fail(c, MOE_E_ARG, "grouped_ffn: NULL pointer");
     if (!row_token && !x_perm) return fail(c, MOE_E_ARG, "grouped_ffn: need x_perm or row_token");
     if ((row_token || s->num_shared > 0) && !x) return fail(c, MOE_E_ARG, "grouped_ffn: x is NULL");
@@ -623,6 +630,7 @@ moe_status moe_grouped_ffn(moe_ctx* c, const moe_shape* s, const void* x_perm, c
 moe_status moe_combine(moe_ctx* c, const moe_shape* s, const void* y_perm, const int32_t* inv_perm, const float* w,
                        const void* y_shared, void* out, void* stream) {
     if (moe_status st = check_common(c, s)) return st;
+    if (s->T == 0) return MOE_OK;   // an empty batch: nothing to do
     if (!y_perm || !inv_perm || !w || !out) return fail(c, MOE_E_ARG, "combine: NULL pointer");
     hipStream_t hs = (hipStream_t)stream;
     StageTimer tm(c, hs, MOE_STAGE_COMBINE);
@@ -634,6 +642,7 @@ moe_status moe_layer(moe_ctx* c, const moe_shape* s, const void* x, const void* 
                      const void* const* w1p, const void* const* w3p, const void* const* w2p, void* out, void* ws,
                      size_t ws_bytes, void* stream) {
     if (moe_status st = check_common(c, s)) return st;
+    if (s->T == 0) return MOE_OK;   // an empty batch: nothing to do
     if (!x || !wg || !out) return fail(c, MOE_E_ARG, "layer: NULL pointer");
     if (moe_status st = check_ws(c, s, ws, ws_bytes)) return st;
     hipStream_t hs = (hipStream_t)stream;
@@ -670,6 +679,7 @@ moe_status moe_layer_chunked(moe_ctx* c, const moe_shape* s, const void* x, cons
                              const void* const* w1p, const void* const* w3p, const void* const* w2p, int32_t max_tokens,
                              void* out, void* ws, size_t ws_bytes, void* stream) {
     if (moe_status st = check_common(c, s)) return st;
+    if (s->T == 0) return MOE_OK;   // an empty batch: nothing to do
     if (max_tokens < 1) return fail(c, MOE_E_ARG, "layer_chunked: max_tokens_per_pass must be >= 1");
     if (!x || !out) return fail(c, MOE_E_ARG, "layer_chunked: NULL pointer");
     const size_t out_row = (size_t)s->H * (c->out_fp32 ? 4 : 2);
@@ -688,6 +698,7 @@ moe_status moe_layer_streamed(moe_ctx* c, const moe_shape* s, const void* x, con
                               size_t slot_bytes, int32_t num_slots, int32_t per_group, void* out, void* ws,
                               size_t ws_bytes, void* stream) {
     if (moe_status st = check_common(c, s)) return st;
+    if (s->T == 0) return MOE_OK;   // an empty batch: nothing to do
     if (!x || !wg || !out || !slots || !hw1 || !hw3 || !hw2) return fail(c, MOE_E_ARG, "layer_streamed: NULL pointer");
     if (moe_status st = check_ws(c, s, ws, ws_bytes)) return st;
     const int E = s->E, Ns = s->num_shared;

@@ -111,6 +111,7 @@ hipError_t launch_permute_index(const moe_shape& s, const int32_t* idx, int32_t*
                                 int32_t* perm, int32_t* inv_perm, int32_t* row_token, hipStream_t st);
 hipError_t launch_permute_gather(const moe_shape& s, const void* x, const int32_t* perm, void* x_perm,
                                  hipStream_t st);
+hipError_t launch_zero_offsets(int E, int32_t* offsets, hipStream_t st);
 // x_perm in 16-row x 32-column blocks (the layout of h), rows past T*k in the last block undefined
 hipError_t launch_permute_gather_tiled(const moe_shape& s, const void* x, const int32_t* row_token, void* x_tiled,
                                        hipStream_t st);

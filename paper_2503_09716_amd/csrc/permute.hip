@@ -173,6 +173,12 @@ hipError_t launch_permute_index(const moe_shape& s, const int32_t* idx, int32_t*
     return hipGetLastError();
 }
 
+// expert_offsets of an empty batch: the scan over zero chunks writes E + 1 zeros
+hipError_t launch_zero_offsets(int E, int32_t* offsets, hipStream_t st) {
+    hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(256), 0, st, (int32_t*)nullptr, 0, E, offsets);
+    return hipGetLastError();
+}
+
 hipError_t launch_permute_gather(const moe_shape& s, const void* x, const int32_t* perm, void* x_perm,
                                  hipStream_t st) {
     const int R = s.T * s.top_k;

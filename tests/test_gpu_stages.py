@@ -392,3 +392,32 @@ def test_error_paths(moe):
     with pytest.raises(MoeError):
         moe.set_option("gemm_wave_rows", 3)
     torch.cuda.synchronize()
+
+
+def test_empty_batch_is_a_no_op(moe):
+    """T = 0: every entry point returns MOE_OK without touching its buffers; moe_permute still
+    reports E empty groups."""
+    from paper_2503_09716_amd import make_shape
+    E, k, H, F = 8, 2, 128, 192
+    shape = make_shape(0, H, F, E, k, num_shared=1, renormalize=False)
+    dev = "cuda"
+    empty16 = torch.empty((0, H), dtype=torch.bfloat16, device=dev)
+    idx = torch.empty((0, k), dtype=torch.int32, device=dev)
+    w = torch.empty((0, k), dtype=torch.float32, device=dev)
+    wg = normal_bf16(9, 0, (H, E), 0.02, dev)
+    ws = torch.empty(1 << 16, dtype=torch.uint8, device=dev)
+    off = torch.full((E + 1,), 7, dtype=torch.int32, device=dev)
+    none_i = torch.empty(0, dtype=torch.int32, device=dev)
+    moe.route(shape, empty16, wg, None, idx, w, None, ws)
+    moe.permute(shape, empty16, idx, empty16, off, none_i, none_i, none_i, ws)
+    torch.cuda.synchronize()
+    assert (off == 0).all()
+    w1 = [normal_bf16(9, 1 + e, (H, F), 0.02, dev) for e in range(E + 1)]
+    w2 = [normal_bf16(9, 20 + e, (F, H), 0.02, dev) for e in range(E + 1)]
+    w1p, w3p, w2p = moe.pack_experts(w1, w1, w2)
+    y = torch.empty((0, H), dtype=torch.float32, device=dev)
+    moe.grouped_ffn(shape, empty16, None, empty16, off, w1p, w3p, w2p, ws, y, y, ws)
+    moe.combine(shape, y, none_i, w, y, empty16)
+    moe.layer(shape, empty16, wg, None, w1p, w3p, w2p, empty16, ws)
+    moe.layer_chunked(shape, empty16, wg, None, w1p, w3p, w2p, 16, empty16, ws)
+    torch.cuda.synchronize()
