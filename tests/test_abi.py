@@ -36,7 +36,8 @@ def test_workspace_bytes_host_logic():
     s2 = binding.make_shape(4096, 4096, 14336, 8, 2, num_shared=1)
     assert binding.workspace_bytes(s2) >= n + 4096 * 14336 * 2 + 4096 * 4096 * 2
     # invalid / unsupported shapes report 0
-    for bad in [binding.make_shape(0, 64, 64, 4, 1), binding.make_shape(8, 64, 64, 4, 5),
+    assert binding.workspace_bytes(binding.make_shape(0, 64, 64, 4, 1)) > 0      # an empty batch is a valid shape
+    for bad in [binding.make_shape(-1, 64, 64, 4, 1), binding.make_shape(8, 64, 64, 4, 5),
                 binding.make_shape(8, 60, 64, 4, 1), binding.make_shape(8, 64, 72, 4, 1),
                 binding.make_shape(8, 64, 64, 300, 1), binding.make_shape(8, 64, 64, 4, 1, num_shared=9)]:
         assert binding.workspace_bytes(bad) == 0
