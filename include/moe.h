@@ -141,8 +141,8 @@ moe_status moe_set_option(moe_ctx* ctx, const char* key, int32_t value);
 moe_status moe_pack_weight(moe_ctx* ctx, const void* w_logical, int32_t rows, int32_t cols,
                            void* w_packed, void* hip_stream);
 
-/* Router (Sec. 2: "a router assigns each token to a subset of experts, typically using a
- * top-k selection strategy").  logit[t,e] = sum_h x[t,h] Wg[h,e] (+ gate_bias[e]) in fp32;
+/* Router (Sec. 2 "MoE inference": every token is sent to its k best-scoring experts).
+ * logit[t,e] = sum_h x[t,h] Wg[h,e] (+ gate_bias[e]) in fp32;
  * p = softmax over all E; the k largest logits are selected (ties: lower expert id),
  * listed in descending order; weight = p (divided by the sum over the selected k when
  * renormalize) * routed_scale.
@@ -155,8 +155,8 @@ moe_status moe_route(moe_ctx* ctx, const moe_shape* shape, const void* x_bf16, c
                      const float* gate_bias, int32_t* topk_idx, float* topk_w, float* logits_or_null,
                      void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Groups the T*k (token, rank) pairs by expert ("tokens routed to an expert", Table 1; the
- * counts are only known at run time, Sec. 4.3).  Order: ascending expert, then ascending
+/* Groups the T*k (token, rank) pairs by expert (Table 1 measures the expert module by the
+ * tokens each expert receives; the counts are only known at run time, Sec. 4.3).  Order: ascending expert, then ascending
  * token.  expert_offsets[e] = first row of expert e (expert_offsets[E] = T*k);
  * perm[r] = t*k+j of the pair at row r; inv_perm[t*k+j] = r; x_perm[r,:] = x[t,:].
  *   topk_idx [T,k] int32 device in (every id in [0,E); not validated)
@@ -168,8 +168,8 @@ moe_status moe_permute(moe_ctx* ctx, const moe_shape* shape, const void* x_bf16,
                        void* x_perm_bf16, int32_t* expert_offsets, int32_t* perm, int32_t* inv_perm,
                        int32_t* row_token_or_null, void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Per-expert SwiGLU FFN over the grouped rows (Sec. 2 "each token is processed by k selected
- * experts"; experts with no rows are skipped), as two grouped bf16 GEMMs with fp32
+/* Per-expert SwiGLU FFN over the grouped rows (Sec. 2: a token goes through each of its k
+ * experts; experts with no rows are skipped, App. A), as two grouped bf16 GEMMs with fp32
  * accumulation: h = silu(X_e W1_e) * (X_e W3_e) rounded to bf16, then y = h W2_e kept in
  * fp32 (or rounded to bf16 under option "y_fp32" = 0).  Shared experts E..E+num_shared-1 run on all T tokens of x; their outputs are
  * summed (one GEMM over the concatenated contraction dimension) into y_shared.
@@ -189,8 +189,8 @@ moe_status moe_grouped_ffn(moe_ctx* ctx, const moe_shape* shape, const void* x_p
                            const void* const* w2p, void* h_scratch_bf16, void* y_perm, void* y_shared,
                            void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Weighted sum back in token order (Sec. 2 "weighted average of the outputs from these
- * experts", plus the shared expert all tokens pass through):
+/* Weighted sum back in token order (Sec. 2: the layer output is the weighted sum of the
+ * selected experts' outputs, plus the shared expert every token goes through):
  *   out[t,:] = sum_{j<k} topk_w[t,j] * y_perm[inv_perm[t*k+j],:] (+ y_shared[t,:]),
  * fp32 accumulation in the order j = 0..k-1 then shared, one store per element, no atomics.
  *   y_perm [T*k,H] and y_shared_or_null [T,H]: fp32 (bf16 under "y_fp32" = 0); inv_perm [T*k];
@@ -199,7 +199,8 @@ moe_status moe_grouped_ffn(moe_ctx* ctx, const moe_shape* shape, const void* x_p
 moe_status moe_combine(moe_ctx* ctx, const moe_shape* shape, const void* y_perm, const int32_t* inv_perm,
                        const float* topk_w, const void* y_shared_or_null, void* out, void* hip_stream);
 
-/* The whole expert module on one stream: route -> permute (indices; the row gather is fused
+/* The whole expert module (Sec. 2 "MoE inference") on the one large batch that module-based
+ * batching accumulates for it (Sec. 4.2), on one stream: route -> permute (indices; the row gather is fused
  * into the first GEMM's loads, or done once into a tiled x_perm: option "x_tiled") -> grouped
  * FFN -> combine.  Same results as the staged
  * calls bit for bit.  All intermediates live in `workspace`.  out [T,H] is bf16, or fp32

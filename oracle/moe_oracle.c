@@ -15,8 +15,9 @@
  * token is handled on its own.  oracle_permute is the separate plain definition (a stable
  * counting sort) of the per-expert grouping the GPU path materialises.
  *
- * Parity pins: see tests/test_oracle_pins.py (brute force, closed forms, dense-SwiGLU
- * special case against an independent library routine, hand-computed example).
+ * Parity pins: see tests/test_oracle_pins.py (brute force, closed forms, dense SwiGLU per
+ * expert against an independent library routine, two hand-computed examples, fp32 and bf16
+ * inputs of the combine against a float64 sum).
  */
 #include <math.h>
 #include <stdint.h>
@@ -34,8 +35,8 @@ static inline float bf16_to_f32(uint16_t b) {
 }
 
 /* ---------------------------------------------------------------------------------------
- * Router (Sec. 2: "a router assigns each token to a subset of experts, typically using a
- * top-k selection strategy").  Reading: linear gate with optional additive bias, softmax
+ * Router (Sec. 2 "MoE inference": every token is sent to its k best-scoring experts).
+ * Reading: linear gate with optional additive bias, softmax
  * over ALL E experts in fp32, top-k chosen on the logits (ties -> lower expert index),
  * selected list in descending logit order; weights are the softmax probabilities of the
  * selected experts, divided by their sum when `renormalize`, then times routed_scale.
@@ -96,8 +97,8 @@ void oracle_route(const uint16_t* x, const uint16_t* wg, const float* bias,
 }
 
 /* ---------------------------------------------------------------------------------------
- * Per-expert grouping of the T*k (token, rank) pairs ("Bsz = average number of tokens
- * routed to an expert", Table 1 caption; counts are unknown until run time, Sec. 4.3).
+ * Per-expert grouping of the T*k (token, rank) pairs (Table 1 measures the expert module by
+ * the number of tokens each expert receives; the counts are only known at run time, Sec. 4.3).
  * Canonical order: ascending expert id, inside an expert ascending token id (a token never
  * picks an expert twice).  Stable counting sort:
  *   offsets[e]      first row of expert e, offsets[E] = T*k
@@ -209,8 +210,8 @@ void oracle_layer(const uint16_t* x, const int32_t* tokens, int ntok,
     }
 }
 
-/* Weighted combine on its own (Sec. 2 "weighted average of the outputs from these
- * experts"): out[t,:] = sum_j w[t,j] * y_perm[inv_perm[t*k+j],:] (+ y_shared[t,:]).
+/* Weighted combine on its own (Sec. 2: the layer output is the weighted sum of the selected
+ * experts' outputs): out[t,:] = sum_j w[t,j] * y_perm[inv_perm[t*k+j],:] (+ y_shared[t,:]).
  * y_perm [R,H] and y_shared [T,H] are the stage's inputs, fp32 when y_is_f32 else bf16 bits;
  * products and sums in fp32 in rank order, shared added last.  out [T,H] fp32. */
 static inline float y_at(const void* y, int y_is_f32, size_t i)

@@ -55,6 +55,33 @@ def test_router_hand_example_and_layer():
     np.testing.assert_allclose(out, np.array(g["expect_out"]), rtol=5e-7)
 
 
+def test_hand_example_mixed_experts():
+    """Two tokens that pick DIFFERENT experts with different non-zero weights, top-2 with
+    renormalisation and one shared expert: an expert mix-up, a dropped shared term, a missing
+    renormalisation or a transposed matrix each change the expected numbers."""
+    g = json.load(open(os.path.join(GOLDEN, "hand_example_mixed_experts.json")))
+    x, wg = bits(g["x"]), bits(g["wg"])
+    w1 = [bits(m) for m in g["w1"]]; w3 = [bits(m) for m in g["w3"]]; w2 = [bits(m) for m in g["w2"]]
+    E, Ns, k = 3, g["num_shared"], g["top_k"]
+    r = orc.route(x, wg, None, k, bool(g["renormalize"]))
+    assert r["idx"].tolist() == g["expect_idx"]
+    np.testing.assert_allclose(r["w"], np.array(g["expect_w"]), rtol=3e-7)
+    out = orc.layer(x, r["idx"], r["w"], w1, w3, w2, E, Ns)
+    np.testing.assert_allclose(out, np.array(g["expect_out"]), rtol=1e-6)
+    # the same experts row by row through the stage-level entry (expert ids 0, 1, 2, 1, shared, shared)
+    ey = g["expect_expert_y"]
+    rows = orc.expert_rows(bits(ey["rows_x"]), np.array(ey["rows_expert"], np.int32), w1, w3, w2)
+    np.testing.assert_allclose(rows, np.array(ey["y"]), rtol=1e-6)
+    # and the combine stage on those rows: y_perm in expert order (e0:t0 | e1:t0,t1 | e2:t1), fp32 input
+    y = np.array(ey["y"], np.float32)
+    y_perm = np.stack([y[0], y[1], y[3], y[2]])
+    inv = np.array([0, 1, 3, 2], np.int32)          # (t0,j0)->e0 row 0, (t0,j1)->e1 row 1, (t1,j0)->e2 row 3, (t1,j1)->e1 row 2
+    o, p, i = orc.permute(r["idx"], E)
+    assert o.tolist() == [0, 1, 3, 4] and i.tolist() == inv.tolist() and p.tolist() == [0, 1, 3, 2]
+    comb = orc.combine(y_perm, inv, r["w"], np.stack([y[4], y[5]]))
+    np.testing.assert_allclose(comb, np.array(g["expect_out"]), rtol=1e-6)
+
+
 @pytest.mark.parametrize("E,k", [(4, 1), (8, 2), (16, 6), (11, 11)])
 def test_router_brute_force_sort(E, k):
     rng = np.random.default_rng(E * 100 + k)
@@ -158,6 +185,32 @@ def test_single_expert_top1_is_dense_swiglu():
     np.testing.assert_allclose(out, ref, rtol=2e-6, atol=1e-6)
     rows = orc.expert_rows(x, np.zeros(T, np.int32), w1, w3, w2)
     np.testing.assert_array_equal(rows, out)
+
+
+def test_expert_rows_mixed_experts_are_each_experts_dense_swiglu():
+    """Stage-level entry with a shuffled multi-expert row -> expert map: every row must be the
+    dense SwiGLU MLP of ITS expert's weights (independent float64 library formulation), and of no
+    other expert's."""
+    rng = np.random.default_rng(31)
+    n, H, F, E = 23, 20, 28, 5        # non-square, so a transposed operand cannot pass
+    x = rnd_bits(rng, (n, H), 1.0)
+    w1 = [rnd_bits(rng, (H, F), 0.3) for _ in range(E)]
+    w3 = [rnd_bits(rng, (H, F), 0.3) for _ in range(E)]
+    w2 = [rnd_bits(rng, (F, H), 0.3) for _ in range(E)]
+    eid = rng.integers(0, E, n).astype(np.int32)
+    eid[:E] = rng.permutation(E)      # every expert appears, in no particular order
+    y = orc.expert_rows(x, eid, w1, w3, w2)
+    dense = [dense_swiglu_torch(x, w1[e], w3[e], w2[e]) for e in range(E)]
+    ref = np.stack([dense[eid[i]][i] for i in range(n)])
+    np.testing.assert_allclose(y, ref, rtol=3e-6, atol=2e-6)
+    # the check has teeth: another expert's output for the same row is far away
+    scale = np.abs(ref).mean()
+    for i in range(n):
+        other = dense[(eid[i] + 1) % E][i]
+        assert np.abs(y[i] - other).max() > 0.05 * scale
+    # the stage-level entry and the layer agree bit for bit when the layer is one expert with weight 1
+    out = orc.layer(x, eid[:, None], np.ones((n, 1), np.float32), w1, w3, w2, E, 0)
+    np.testing.assert_array_equal(out, y)
 
 
 def test_identical_experts_reduce_to_dense():
@@ -268,6 +321,39 @@ def test_combine_pins():
     np.testing.assert_array_equal(o1, bf16_bits_to_f32(y[:T])[inv1])
     # linear in w (power-of-two scale is exact)
     np.testing.assert_array_equal(orc.combine(y, inv, 2 * w), 2 * orc.combine(y, inv, w))
+
+
+def test_combine_fp32_inputs():
+    """The float32-input form of the combine (what the down projection hands over by default):
+    values with full 24-bit mantissas against the float64 sum; gather and linearity bit-exact."""
+    rng = np.random.default_rng(22)
+    T, H, k = 11, 14, 3
+    y = (rng.standard_normal((T * k, H)) * np.pi).astype(np.float32)      # full mantissas, not bf16-representable
+    assert (f32_to_bf16_bits(y).astype(np.uint32) << 16 != y.view(np.uint32)).mean() > 0.9
+    ys = (rng.standard_normal((T, H)) * np.e).astype(np.float32)
+    inv = rng.permutation(T * k).astype(np.int32)
+    w = rng.random((T, k)).astype(np.float32)
+    out = orc.combine(y, inv, w, ys)
+    ref = (w.astype(np.float64)[:, :, None] * y.astype(np.float64)[inv.reshape(T, k)]).sum(1) + ys.astype(np.float64)
+    np.testing.assert_allclose(out, ref, rtol=1e-6, atol=1e-6)
+    # every element is read where it is: a one-hot y_perm lands in exactly one output element
+    for (r, h) in [(0, 0), (5, 13), (T * k - 1, 7), (17, 1)]:
+        hot = np.zeros((T * k, H), np.float32); hot[r, h] = 1.0
+        o = orc.combine(hot, inv, w)
+        t, j = divmod(int(np.nonzero(inv == r)[0][0]), k)
+        expect = np.zeros((T, H), np.float32); expect[t, h] = w[t, j]
+        np.testing.assert_array_equal(o, expect)
+    # k = 1, w = 1: a pure row gather, bit-exact (float32 values pass through unrounded)
+    inv1 = rng.permutation(T).astype(np.int32)
+    np.testing.assert_array_equal(orc.combine(y[:T], inv1, np.ones((T, 1), np.float32)), y[:T][inv1])
+    # shared rows are added with weight 1 to the right token
+    z = np.zeros((T * k, H), np.float32)
+    np.testing.assert_array_equal(orc.combine(z, inv, w, ys), ys)
+    # power-of-two scale is exact; bf16-representable float32 input equals the bf16-bits form
+    np.testing.assert_array_equal(orc.combine(y, inv, 2 * w), 2 * orc.combine(y, inv, w))
+    yb = rnd_bits(rng, (T * k, H), 1.0); ysb = rnd_bits(rng, (T, H), 1.0)
+    np.testing.assert_array_equal(orc.combine(bf16_bits_to_f32(yb), inv, w, bf16_bits_to_f32(ysb)),
+                                  orc.combine(yb, inv, w, ysb))
 
 
 def test_oracle_reports_threads():
