@@ -24,12 +24,15 @@ def host_u16(t: torch.Tensor) -> np.ndarray:
     return torch_bf16_to_u16(t)
 
 
-def compare_routing(gpu_idx: np.ndarray, gpu_w: np.ndarray, ref: dict, top_k: int):
-    """ref: oracle.route(..., want_logits=True) for the same tokens.  Returns a report; raises on an
-    unexcused mismatch.  A set mismatch at token t is excused iff the oracle's k-th and (k+1)-th
-    largest logits differ by < TIE_MARGIN; an order-only mismatch iff every displaced pair of
-    logits differs by < TIE_MARGIN."""
-    idx_o, w_o, logit = ref["idx"], ref["w"], ref["logits"]
+def compare_routing(gpu_idx: np.ndarray, gpu_w: np.ndarray, ref: dict, top_k: int, renormalize: bool = True,
+                    routed_scale: float = 1.0):
+    """ref: oracle.route(..., want_logits=True, want_probs=True) for the same tokens.  Returns a
+    report; raises on an unexcused mismatch.  A set mismatch at token t is excused iff the oracle's
+    k-th and (k+1)-th largest logits differ by < TIE_MARGIN; an order-only mismatch iff every
+    displaced pair of logits differs by < TIE_MARGIN.  The weights of an excused token must still
+    be the oracle's softmax probabilities at the experts the GPU chose (renormalised over them
+    when the layer renormalises)."""
+    idx_o, w_o, logit, probs = ref["idx"], ref["w"], ref["logits"], ref["probs"]
     n, E = logit.shape
     bad = np.nonzero((gpu_idx != idx_o).any(axis=1))[0]
     excused_set, excused_order = [], []
@@ -49,6 +52,12 @@ def compare_routing(gpu_idx: np.ndarray, gpu_w: np.ndarray, ref: dict, top_k: in
     good = np.setdiff1d(np.arange(n), bad)
     if len(good):
         np.testing.assert_allclose(gpu_w[good], w_o[good], rtol=W_RTOL, atol=1e-7)
+    if len(bad):
+        sel = np.take_along_axis(probs[bad].astype(np.float64), gpu_idx[bad].astype(np.int64), axis=1)
+        if renormalize:
+            sel = sel / sel.sum(axis=1, keepdims=True)
+        np.testing.assert_allclose(gpu_w[bad], sel * routed_scale, rtol=W_RTOL, atol=1e-7,
+                                   err_msg="weights of near-tie tokens are not the oracle's probabilities at the chosen experts")
     so = np.sort(logit, axis=1)[:, ::-1]
     near = int((so[:, top_k - 1] - so[:, top_k] < TIE_MARGIN).sum()) if top_k < E else 0
     return {"tokens": int(n), "mismatch_set_excused": excused_set, "mismatch_order_excused": excused_order,
@@ -82,13 +91,16 @@ def assert_output(out_gpu: np.ndarray, out_ref: np.ndarray, what: str = "output"
 
 
 def assert_output_bf16(out_gpu: np.ndarray, out_ref: np.ndarray, what: str = "output"):
-    """Per-element bound for a result stored in bf16: the fp32 result may be off by the error bar
-    (OUT_BAR x RMS), and rounding it to bf16 (8 significant bits, round to nearest even) moves it
-    by at most 2^-8 of its own magnitude, which is at most |ref| + the bar."""
+    """Per-element bound for a result stored in bf16: the fp32 result v may be off by the error bar
+    (OUT_BAR x RMS), so |v| <= |ref| + bar, and rounding v to bf16 (8 significant bits, round to
+    nearest even) moves it by at most half a bf16 step of its binade: 2^(floor(log2 |v|) - 8)."""
     ref = out_ref.astype(np.float64)
     rms = float(np.sqrt((ref ** 2).mean()))
     err = np.abs(out_gpu.astype(np.float64) - ref)
-    bound = OUT_BAR * rms + (np.abs(ref) + OUT_BAR * rms) * 2.0 ** -8
+    vmax = np.abs(ref) + OUT_BAR * rms
+    _, ex = np.frexp(vmax)                               # vmax = m * 2^ex, m in [0.5, 1): floor(log2 vmax) = ex - 1
+    half_step = np.ldexp(1.0, np.maximum(ex - 1, -126) - 8)
+    bound = OUT_BAR * rms + half_step
     worst = float((err / bound).max())
     assert worst <= 1.0, "%s: bf16 result off by %.3f x its bound" % (what, worst)
     return output_report(out_gpu, out_ref)
@@ -136,7 +148,7 @@ class GpuLayer:
     def oracle_route(self, tokens=None):
         cfg = self.cfg
         return orc.route(self.hx, self.hwg, self.li.bias, cfg.top_k, cfg.renormalize, cfg.routed_scale,
-                         tokens=tokens, want_logits=True)
+                         tokens=tokens, want_logits=True, want_probs=True)
 
     def oracle_layer(self, idx, w, tokens=None):
         cfg = self.cfg
@@ -166,7 +178,7 @@ def check_layer_against_oracle(gl: GpuLayer, out: torch.Tensor, tokens=None, che
     rt_tokens = None if (check_all_routing or tokens is None) else tokens
     ref = gl.oracle_route(rt_tokens)
     sel = slice(None) if rt_tokens is None else rt_tokens
-    report["routing"] = compare_routing(idx[sel], w[sel], ref, cfg.top_k)
+    report["routing"] = compare_routing(idx[sel], w[sel], ref, cfg.top_k, cfg.renormalize, cfg.routed_scale)
     # FFN + combine: the oracle runs with the GPU's routing, so an excused near-tie cannot fail it
     if tokens is None:
         tokens = np.arange(cfg.T, dtype=np.int32)
@@ -180,22 +192,59 @@ def check_layer_against_oracle(gl: GpuLayer, out: torch.Tensor, tokens=None, che
     return report
 
 
+TILE_ROWS = (128, 256, 320)      # every m-tile height the grouped GEMMs use for full tiles
+
+
 def sample_tokens(idx: np.ndarray, E: int, n: int, seed: int) -> np.ndarray:
-    """About n tokens: for each non-empty expert one at random plus the ones behind the first and
-    the last row of its group (the last row sits in the group's tail tile), the first and the last
-    16 tokens (the tail tile of the shared experts), the rest uniformly at random."""
+    """At least n tokens chosen so that EVERY m-tile of every expert's row group holds a checked
+    row, whichever tile height a launch uses: per group (rows are in ascending token order) one
+    random row from each block of 128, of 256 and of 320 rows; the rows on both sides of the first
+    tile boundaries (127..129, 255..257, 319..321); the first and the last row; the rows on both
+    sides of the place where a short tail (the rows past the last multiple of 256) joins the last
+    full tile.  The same positions of the token range itself cover the shared experts, whose
+    groups are all T tokens.  The rest uniformly at random."""
     rng = np.random.default_rng(seed)
-    T = idx.shape[0]
-    flat_tok = np.repeat(np.arange(T), idx.shape[1])
-    flat_e = idx.reshape(-1)
-    order = rng.permutation(len(flat_e))
-    seen = np.full(E, -1, np.int64)
-    seen[flat_e[order]] = flat_tok[order]
-    first = np.full(E, -1, np.int64)
-    last = np.full(E, -1, np.int64)
-    last[flat_e] = flat_tok                    # rows of a group are in token order: highest token = last row
-    first[flat_e[::-1]] = flat_tok[::-1]
-    chosen = np.concatenate([seen, first, last, np.arange(min(16, T)), np.arange(max(0, T - 16), T)])
-    chosen = chosen[chosen >= 0]
-    rest = rng.permutation(T)[:max(0, n - len(np.unique(chosen)))]
+    T, k = idx.shape
+    flat_e = idx.reshape(-1).astype(np.int64)
+    flat_tok = np.repeat(np.arange(T, dtype=np.int64), k)
+    order = np.lexsort((flat_tok, flat_e))               # rows of the permuted batch: by expert, then token
+    row_tok = flat_tok[order]
+    off = np.concatenate([[0], np.cumsum(np.bincount(flat_e, minlength=E))])
+
+    def positions(rows: int) -> np.ndarray:
+        """Row positions inside a group of `rows` rows."""
+        pos = [0, rows - 1]
+        for tm in TILE_ROWS:
+            starts = np.arange(0, rows, tm)
+            pos.extend((starts + rng.integers(0, np.minimum(tm, rows - starts))).tolist())
+            pos.extend([tm - 1, tm, tm + 1])
+        full = (rows // 256) * 256
+        pos.extend([full - 1, full, full + 1, full - 256, full - 257])
+        p = np.array(pos, dtype=np.int64)
+        return np.unique(p[(p >= 0) & (p < rows)])
+
+    chosen = [positions(T)]                                          # shared experts: the token range itself
+    for e in range(E):
+        rows = int(off[e + 1] - off[e])
+        if rows:
+            chosen.append(row_tok[off[e] + positions(rows)])
+    chosen = np.unique(np.concatenate(chosen))
+    rest = rng.permutation(T)[:max(0, n - len(chosen))]
     return np.unique(np.concatenate([chosen, rest])).astype(np.int32)
+
+
+def tiles_without_a_sampled_row(idx: np.ndarray, E: int, tokens: np.ndarray, tile_rows: int) -> int:
+    """Number of m-tiles (blocks of tile_rows rows of an expert's group) none of whose rows belongs
+    to a sampled token; 0 means the sample reaches every tile."""
+    T, k = idx.shape
+    flat_e = idx.reshape(-1).astype(np.int64)
+    flat_tok = np.repeat(np.arange(T, dtype=np.int64), k)
+    order = np.lexsort((flat_tok, flat_e))
+    hit = np.isin(flat_tok[order], tokens)
+    off = np.concatenate([[0], np.cumsum(np.bincount(flat_e, minlength=E))])
+    missing = 0
+    for e in range(E):
+        for r0 in range(int(off[e]), int(off[e + 1]), tile_rows):
+            if not hit[r0:min(r0 + tile_rows, int(off[e + 1]))].any():
+                missing += 1
+    return missing

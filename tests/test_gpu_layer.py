@@ -161,14 +161,17 @@ def test_layer_metamorphic_exact(moe):
     assert (z.float() == 0).all()
 
 
-FULL = [("C2", 512), ("C3", 384), ("C4", 768), ("C5", 1024), ("C5b", 384)]
+# nsample = 0: every token goes through the oracle
+FULL = [("C2", 0), ("C3", 512), ("C4", 0), ("C5", 1024), ("C5b", 512)]
 
 
 @pytest.mark.parametrize("name,nsample", FULL)
 def test_layer_full_size_sampled(moe, name, nsample):
-    """Full-size workload: routing and permutation for ALL tokens, FFN + combine on a seeded sample
-    of tokens that covers every non-empty expert (tokens are independent, so per-token oracle
-    outputs are exact)."""
+    """Full-size workload in the launch configuration bench.py times: routing and permutation for
+    ALL tokens; FFN + combine for ALL tokens on the Mixtral-8x7B- and DeepSeek-V2-Lite-shaped
+    workloads, and on the others for a seeded sample of tokens that puts a checked row into every
+    m-tile of every expert's group, at every tile height the GEMMs use (tokens are independent,
+    so per-token oracle outputs are exact)."""
     cfg = get_config(name)
     t0 = time.time()
     say("full", cfg)
@@ -178,7 +181,14 @@ def test_layer_full_size_sampled(moe, name, nsample):
     out, out16 = gl.run_layer_both()
     assert torch.isfinite(out).all()
     idx = moe.layer_views(gl.shape, gl.ws)["topk_idx"].cpu().numpy()
-    tokens = P.sample_tokens(idx, cfg.E, nsample, cfg.seed)
+    if nsample:
+        tokens = P.sample_tokens(idx, cfg.E, nsample, cfg.seed)
+        for tm in P.TILE_ROWS:
+            assert P.tiles_without_a_sampled_row(idx, cfg.E, tokens, tm) == 0
+            assert P.tiles_without_a_sampled_row(np.zeros((cfg.T, 1), np.int64), 1, tokens, tm) == 0   # shared experts
+    else:
+        tokens = np.arange(cfg.T, dtype=np.int32)
+    say("  oracle on %d of %d tokens" % (len(tokens), cfg.T))
     t1 = time.time()
     rep = P.check_layer_against_oracle(gl, out, tokens=tokens, check_all_routing=True, out16=out16)
     rep["sampled_tokens"] = int(len(tokens))

@@ -61,8 +61,8 @@ def test_route(moe, name, over):
     moe.route(shape, li.x, li.wg, bias, idx, w, logits, ws)
     torch.cuda.synchronize()
     ref = orc.route(torch_bf16_to_u16(li.x), torch_bf16_to_u16(li.wg), li.bias, cfg.top_k, cfg.renormalize,
-                    cfg.routed_scale, want_logits=True)
-    rep = P.compare_routing(idx.cpu().numpy(), w.cpu().numpy(), ref, cfg.top_k)
+                    cfg.routed_scale, want_logits=True, want_probs=True)
+    rep = P.compare_routing(idx.cpu().numpy(), w.cpu().numpy(), ref, cfg.top_k, cfg.renormalize, cfg.routed_scale)
     say(rep)
     err = np.abs(logits.cpu().numpy() - ref["logits"]).max()
     assert err < 5e-6, err
