@@ -195,14 +195,15 @@ def check_layer_against_oracle(gl: GpuLayer, out: torch.Tensor, tokens=None, che
 TILE_ROWS = (128, 256, 320)      # every m-tile height the grouped GEMMs use for full tiles
 
 
-def sample_tokens(idx: np.ndarray, E: int, n: int, seed: int) -> np.ndarray:
+def sample_tokens(idx: np.ndarray, E: int, n: int, seed: int, every_tile: bool = True) -> np.ndarray:
     """At least n tokens chosen so that EVERY m-tile of every expert's row group holds a checked
     row, whichever tile height a launch uses: per group (rows are in ascending token order) one
     random row from each block of 128, of 256 and of 320 rows; the rows on both sides of the first
     tile boundaries (127..129, 255..257, 319..321); the first and the last row; the rows on both
     sides of the place where a short tail (the rows past the last multiple of 256) joins the last
     full tile.  The same positions of the token range itself cover the shared experts, whose
-    groups are all T tokens.  The rest uniformly at random."""
+    groups are all T tokens.  The rest uniformly at random.  every_tile=False keeps only the
+    boundary rows of each group (no row per block): about 20 tokens per expert."""
     rng = np.random.default_rng(seed)
     T, k = idx.shape
     flat_e = idx.reshape(-1).astype(np.int64)
@@ -216,7 +217,8 @@ def sample_tokens(idx: np.ndarray, E: int, n: int, seed: int) -> np.ndarray:
         pos = [0, rows - 1]
         for tm in TILE_ROWS:
             starts = np.arange(0, rows, tm)
-            pos.extend((starts + rng.integers(0, np.minimum(tm, rows - starts))).tolist())
+            if every_tile:
+                pos.extend((starts + rng.integers(0, np.minimum(tm, rows - starts))).tolist())
             pos.extend([tm - 1, tm, tm + 1])
         full = (rows // 256) * 256
         pos.extend([full - 1, full, full + 1, full - 256, full - 257])

@@ -209,7 +209,11 @@ def test_layer_full_size_sampled(moe, name, nsample):
 def test_layer_at_the_4_gib_limit(moe):
     """Largest permuted batch the library takes for H = 2048 (x_perm just under 4 GiB, the limit of
     one buffer descriptor; fp32 y_perm is then 8.6 GB, beyond 32-bit byte offsets): sampled tokens,
-    among them the last rows of every group, against the oracle.  One row more is refused."""
+    among them the first and last rows of every group and the rows around its last tile boundary,
+    against the oracle.  One row more is refused.
+    (A test of addressing, so a few hundred tokens: with experts only 64 wide, the unavoidable bf16
+    rounding of h alone reaches 2.4e-2 x RMS somewhere among 20000 tokens, which is why this shape
+    is not sampled tile by tile like the named workloads.)"""
     from paper_2503_09716_amd import MoeError, shape_of
     cfg = scaled_config("C2", T=524_000, H=2048, F=64, E=8, top_k=2)
     assert cfg.T * cfg.top_k * cfg.H * 2 < 2 ** 32 <= (cfg.T + 288) * cfg.top_k * cfg.H * 2
@@ -218,7 +222,7 @@ def test_layer_at_the_4_gib_limit(moe):
     out, out16 = gl.run_layer_both()
     assert torch.isfinite(out).all()
     idx = moe.layer_views(gl.shape, gl.ws)["topk_idx"].cpu().numpy()
-    tokens = P.sample_tokens(idx, cfg.E, 256, cfg.seed)
+    tokens = P.sample_tokens(idx, cfg.E, 256, cfg.seed, every_tile=False)
     say(json.dumps(P.check_layer_against_oracle(gl, out, tokens=tokens, check_all_routing=False, out16=out16)))
     too_big = shape_of(scaled_config("C2", T=cfg.T + 288, H=2048, F=64, E=8, top_k=2))
     from paper_2503_09716_amd.binding import workspace_bytes
