@@ -210,6 +210,21 @@ moe_status moe_layer(moe_ctx* ctx, const moe_shape* shape, const void* x_bf16, c
                      const void* const* w2p, void* out, void* workspace, size_t workspace_bytes,
                      void* hip_stream);
 
+/* moe_layer for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same
+ * results bit for bit; the intermediates live in a scratch array of MOE_STATIC_WORKSPACE_BYTES
+ * that is part of the library's device image (each GPU the library runs on holds one copy until
+ * the process ends).  The call allocates nothing and frees nothing.
+ * Limit: moe_workspace_bytes(shape) <= MOE_STATIC_WORKSPACE_BYTES (small and decode-sized batches;
+ * e.g. 256 tokens of H = 512, F = 1024 with 8 experts), else MOE_E_WORKSPACE and nothing is enqueued.
+ * All contexts and calls on one GPU share that GPU's array: two calls that overlap in time on
+ * one GPU (different streams, or different contexts) race; calls on one stream are safe.  The
+ * array keeps the previous call's contents; the layer never reads a region before writing it. */
+#define MOE_STATIC_WORKSPACE_BYTES ((size_t)32 << 20)
+moe_status moe_layer_static(moe_ctx* ctx, const moe_shape* shape, const void* x_bf16, const void* wg_bf16,
+                            const float* gate_bias, const void* const* w1p, const void* const* w3p,
+                            const void* const* w2p, void* out, void* hip_stream);
+
 /* Accumulation of micro-batches (Sec. 4.2: the hidden states that leave attention in micro-batches
  * of b_a sequences are accumulated until the expert module's batch B is reached): appends
  * `rows` rows of x_microbatch [rows, H] bf16 (device) to staging [capacity_rows, H] bf16 (device)

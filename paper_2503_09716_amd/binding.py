@@ -15,11 +15,13 @@ import torch
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libmoe_mi355.so")
 
+STATIC_WORKSPACE_BYTES = 32 << 20   # MOE_STATIC_WORKSPACE_BYTES of include/moe.h
+
 STAGES = ["route", "permute_index", "permute_gather", "plan", "ffn_gate_up", "ffn_down", "combine"]
 
 EXPORTS = [
     "moe_create", "moe_destroy", "moe_last_error", "moe_workspace_bytes", "moe_h_scratch_bytes", "moe_set_option", "moe_pack_weight",
-    "moe_route", "moe_permute", "moe_grouped_ffn", "moe_combine", "moe_layer", "moe_layer_views",
+    "moe_route", "moe_permute", "moe_grouped_ffn", "moe_combine", "moe_layer", "moe_layer_static", "moe_layer_views",
     "moe_layer_streamed", "moe_stream_stats", "moe_estimate_streamed_ms", "moe_accumulate", "moe_layer_chunked",
     "moe_profile_enable", "moe_profile_read",
 ]
@@ -67,6 +69,7 @@ def load_library():
     lib.moe_grouped_ffn.argtypes = [C.c_void_p, sp, vp, i32p, vp, i32p, tab, tab, tab, vp, vp, vp, vp, C.c_size_t, vp]
     lib.moe_combine.argtypes = [C.c_void_p, sp, vp, i32p, f32p, vp, vp, vp]
     lib.moe_layer.argtypes = [C.c_void_p, sp, vp, vp, f32p, tab, tab, tab, vp, vp, C.c_size_t, vp]
+    lib.moe_layer_static.argtypes = [C.c_void_p, sp, vp, vp, f32p, tab, tab, tab, vp, vp]
     lib.moe_layer_streamed.argtypes = [C.c_void_p, sp, vp, vp, f32p, tab, tab, tab, vp, C.c_size_t, C.c_int32, C.c_int32,
                                        vp, vp, C.c_size_t, vp]
     lib.moe_accumulate.argtypes = [C.c_void_p, vp, C.c_int32, C.c_int32, C.POINTER(C.c_int32), vp, C.c_int32, vp]
@@ -205,6 +208,12 @@ class Moe:
         t1, t3, t2 = tables if tables is not None else (_table(w1p), _table(w3p), _table(w2p))
         self._check(self.lib.moe_layer(self.h, C.byref(shape), _ptr(x), _ptr(wg), _ptr(bias), t1, t3, t2,
                                        _ptr(out), _ptr(workspace), workspace.numel(), _stream()))
+
+    def layer_static(self, shape, x, wg, bias, w1p, w3p, w2p, out, tables=None):
+        """moe_layer with the library's built-in scratch as workspace (allocates nothing)."""
+        t1, t3, t2 = tables if tables is not None else (_table(w1p), _table(w3p), _table(w2p))
+        self._check(self.lib.moe_layer_static(self.h, C.byref(shape), _ptr(x), _ptr(wg), _ptr(bias), t1, t3, t2,
+                                              _ptr(out), _stream()))
 
     def layer_streamed(self, shape, x, wg, bias, host_w1p, host_w3p, host_w2p, slots, num_slots, experts_per_group,
                        out, workspace):

@@ -10,6 +10,13 @@
 
 using namespace moe;
 
+// Scratch for moe_layer_static: callers that must not allocate get their workspace from here.
+// Every GPU the library runs on holds its own copy of the array until the process ends.  In
+// host code the array's name is only a handle for hipGetSymbolAddress (done once per context
+// in moe_create, with the context's device current); kernels are given the address it returns.
+constexpr size_t STATIC_SCRATCH_BYTES = MOE_STATIC_WORKSPACE_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
 namespace {
 
 constexpr int TABLE_SLOTS = 8;
@@ -31,6 +38,7 @@ struct moe_ctx {
     bool y_fp32 = true;    // dtype of y_perm / y_shared in the staged calls
     int layer_y = -1;      // moe_layer's y_perm: 1 fp32, 0 bf16, -1 choose (its y_shared is always fp32)
     bool out_fp32 = false; // dtype of the layer output
+    char* static_ws = nullptr;  // this device's address of `scratch`
     // Ring of device pointer tables [3][MAX_GROUPS] (W1p, W3p, W2p), each with a pinned host
     // staging copy and an event marking the end of its upload.
     void** d_tab[TABLE_SLOTS] = {nullptr};
@@ -479,6 +487,24 @@ moe_status run_front(moe_ctx* c, const moe_shape& s, const void* x, const void* 
     return MOE_OK;
 }
 
+// The whole layer with its intermediates in `ws` (validated by the caller).
+moe_status layer_with_workspace(moe_ctx* c, const moe_shape* s, const void* x, const void* wg, const float* bias,
+                                const void* const* w1p, const void* const* w3p, const void* const* w2p, void* out,
+                                char* ws, hipStream_t hs) {
+    void** tab = nullptr;
+    if (moe_status st = weight_table(c, s->E + s->num_shared, w1p, w3p, w2p, hs, &tab)) return st;
+    LayerFront f;
+    if (moe_status st = run_front(c, *s, x, wg, bias, ws, hs, &f)) return st;
+    if (moe_status st = run_ffn(c, *s, nullptr, f.row_token, x, f.x_tiled, f.offsets, tab, ws, f.h, f.y_perm,
+                                f.y_shared, f.y32, true, hs))
+        return st;
+    {
+        StageTimer tm(c, hs, MOE_STAGE_COMBINE);
+        HIP_TRY(c, launch_combine(*s, f.y_perm, f.inv_perm, f.topk_w, f.y_shared, out, f.y32, true, c->out_fp32, hs));
+    }
+    return MOE_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -491,6 +517,8 @@ moe_status moe_create(moe_ctx** out, int device) {
     c->device = device;
     c->tab_shadow.assign(3 * MAX_GROUPS, nullptr);
     bool ok = ffn_gemm_init() == hipSuccess;
+    ok = ok && hipGetSymbolAddress((void**)&c->static_ws, HIP_SYMBOL(scratch)) == hipSuccess && c->static_ws != nullptr &&
+         ((uintptr_t)c->static_ws & 255) == 0;
     ok = ok && hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking) == hipSuccess &&
          hipHostMalloc((void**)&c->h_offsets, (MAX_GROUPS + 1) * sizeof(int32_t), hipHostMallocDefault) == hipSuccess;
     for (int i = 0; i < MAX_SLOTS && ok; ++i)
@@ -645,19 +673,22 @@ moe_status moe_layer(moe_ctx* c, const moe_shape* s, const void* x, const void* 
     if (s->T == 0) return MOE_OK;   // an empty batch: nothing to do
     if (!x || !wg || !out) return fail(c, MOE_E_ARG, "layer: NULL pointer");
     if (moe_status st = check_ws(c, s, ws, ws_bytes)) return st;
-    hipStream_t hs = (hipStream_t)stream;
-    void** tab = nullptr;
-    if (moe_status st = weight_table(c, s->E + s->num_shared, w1p, w3p, w2p, hs, &tab)) return st;
-    LayerFront f;
-    if (moe_status st = run_front(c, *s, x, wg, bias, (char*)ws, hs, &f)) return st;
-    if (moe_status st = run_ffn(c, *s, nullptr, f.row_token, x, f.x_tiled, f.offsets, tab, (char*)ws, f.h, f.y_perm,
-                                f.y_shared, f.y32, true, hs))
-        return st;
-    {
-        StageTimer tm(c, hs, MOE_STAGE_COMBINE);
-        HIP_TRY(c, launch_combine(*s, f.y_perm, f.inv_perm, f.topk_w, f.y_shared, out, f.y32, true, c->out_fp32, hs));
-    }
-    return MOE_OK;
+    return layer_with_workspace(c, s, x, wg, bias, w1p, w3p, w2p, out, (char*)ws, (hipStream_t)stream);
+}
+
+moe_status moe_layer_static(moe_ctx* c, const moe_shape* s, const void* x, const void* wg, const float* bias,
+                            const void* const* w1p, const void* const* w3p, const void* const* w2p, void* out,
+                            void* stream) {
+    if (moe_status st = check_common(c, s)) return st;
+    if (s->T == 0) return MOE_OK;   // an empty batch: nothing to do
+    if (!x || !wg || !out) return fail(c, MOE_E_ARG, "layer_static: NULL pointer");
+    const size_t need = make_layout(*s).total;
+    if (need > STATIC_SCRATCH_BYTES)
+        return fail(c, MOE_E_WORKSPACE, "layer_static: this shape needs %zu bytes of workspace, the built-in scratch holds %zu; "
+                                        "use moe_layer with a caller-owned workspace", need, STATIC_SCRATCH_BYTES);
+    // Nothing in the layer relies on the workspace's previous contents: every region is written
+    // by the kernel that precedes its first reader, so the last call's leftovers need no clearing.
+    return layer_with_workspace(c, s, x, wg, bias, w1p, w3p, w2p, out, c->static_ws, (hipStream_t)stream);
 }
 
 moe_status moe_accumulate(moe_ctx* c, void* staging, int32_t capacity, int32_t H, int32_t* filled, const void* x_mb,

@@ -26,6 +26,12 @@ def test_library_exports_every_declared_symbol():
     assert sorted(binding.EXPORTS) == names
 
 
+def test_static_scratch_size_matches_the_header():
+    text = open(os.path.join(ROOT, "include", "moe.h")).read()
+    m = re.search(r"#define\s+MOE_STATIC_WORKSPACE_BYTES\s+\(\(size_t\)(\d+)\s*<<\s*(\d+)\)", text)
+    assert m and int(m.group(1)) << int(m.group(2)) == binding.STATIC_WORKSPACE_BYTES
+
+
 def test_workspace_bytes_host_logic():
     s = binding.make_shape(4096, 4096, 14336, 8, 2)
     n = binding.workspace_bytes(s)
