@@ -98,7 +98,7 @@ size_t moe_h_scratch_bytes(const moe_shape* shape);
 /* Tuning knobs (host call).  Unknown key or out-of-range value: MOE_E_ARG.
  *   "gemm_waves"      4 | 8   wavefronts per GEMM workgroup (one or two per SIMD)
  *   "gemm_wave_rows"  1|2|4   rows of the wave grid (rows x waves/rows): 1 or 2 with 4 waves (4 rows
- *                             is treated as 2), 2 or 4 with 8 waves (1 row is treated as 2)
+ *                             is treated as 1), 2 or 4 with 8 waves (1 row is treated as 2)
  *   "gemm_group_m"    0..64   m-tiles swept together along n (L2 reuse of weight panels); 0 (default) picks
  *                             the typical number of tiles per expert, between 4 and 8
  *   "xcd_remap"       0 | 1   give each XCD runs of consecutive tiles
@@ -122,8 +122,6 @@ size_t moe_h_scratch_bytes(const moe_shape* shape);
  *                             place, 1: tall tiles run after the regular ones (when "tails_last"), 0: off,
  *                             -1 (default): 2 for up to 8 tiles per expert on average, else 1.  Same results
  *                             bit for bit.
- *   "probe_k_resident" 0 | 1  timing probe only: the GEMMs re-read their first K tile at every K step
- *                             (operands stay cache resident, RESULTS ARE MEANINGLESS); default 0
  *   "y_fp32"          0 | 1   staged calls: dtype of y_perm / y_shared: 1 (default) fp32, 0 bf16.  bf16 halves the
  *                             traffic of the down projection's store and of the combine's loads, but
  *                             rounds each expert output to 8 mantissa bits before the weighted sum
@@ -132,7 +130,10 @@ size_t moe_h_scratch_bytes(const moe_shape* shape);
  *                             share of the output), fp32 otherwise.
  *                             Its y_shared is always fp32.
  *   "out_fp32"        0 | 1   dtype of the layer output written by moe_combine / moe_layer:
- *                             0 (default) bf16 = round-to-nearest-even of the fp32 sum, 1 fp32 */
+ *                             0 (default) bf16 = round-to-nearest-even of the fp32 sum, 1 fp32
+ *   "gate_packed"     0 | 1   1: for shapes with E > 16 the wg_bf16 argument of moe_route and of every moe_layer
+ *                             variant is the packed gate matrix made by moe_pack_gate (the router then skips
+ *                             its per-call packing launch); shapes with E <= 16 are not affected.  Default 0. */
 moe_status moe_set_option(moe_ctx* ctx, const char* key, int32_t value);
 
 /* One-time weight packing: w_logical [rows, cols] bf16 (device; rows = contraction dimension)
@@ -141,12 +142,22 @@ moe_status moe_set_option(moe_ctx* ctx, const char* key, int32_t value);
 moe_status moe_pack_weight(moe_ctx* ctx, const void* w_logical, int32_t rows, int32_t cols,
                            void* w_packed, void* hip_stream);
 
+/* One-time packing of the gate matrix for shapes whose router runs on the matrix cores (E > 16):
+ * wg_bf16 [H,E] logical (device) -> wg_packed (device, moe_gate_packed_bytes(shape) bytes: the
+ * expert count padded to a multiple of 32 with zero rows, in the packed weight layout).  The gate
+ * matrix is static like the expert weights, so this cost is outside the timed path; pass the
+ * result as wg_bf16 under option "gate_packed" = 1.  moe_gate_packed_bytes is 0 and moe_pack_gate
+ * returns MOE_E_ARG when E <= 16 (the streaming router reads the logical layout). */
+size_t moe_gate_packed_bytes(const moe_shape* shape);
+moe_status moe_pack_gate(moe_ctx* ctx, const moe_shape* shape, const void* wg_bf16, void* wg_packed, void* hip_stream);
+
 /* Router (Sec. 2 "MoE inference": every token is sent to its k best-scoring experts).
  * logit[t,e] = sum_h x[t,h] Wg[h,e] (+ gate_bias[e]) in fp32;
  * p = softmax over all E; the k largest logits are selected (ties: lower expert id),
  * listed in descending order; weight = p (divided by the sum over the selected k when
  * renormalize) * routed_scale.
- *   x_bf16 [T,H] device, wg_bf16 [H,E] device (logical layout), gate_bias [E] fp32 device or NULL
+ *   x_bf16 [T,H] device, wg_bf16 [H,E] device (logical layout; packed under option "gate_packed"),
+ *   gate_bias [E] fp32 device or NULL
  *   topk_idx [T,k] int32 device out, topk_w [T,k] fp32 device out,
  *   logits_or_null [T,E] fp32 device out (for near-tie reports) or NULL
  *   workspace: device, at least moe_workspace_bytes(shape) (used when E > 16: the gate GEMM then
@@ -295,6 +306,21 @@ moe_status moe_layer_views(const moe_shape* shape, void* workspace, int32_t** to
  * between reads (further ones are dropped). */
 moe_status moe_profile_enable(moe_ctx* ctx, int32_t on);
 moe_status moe_profile_read(moe_ctx* ctx, double* ms_sum, int32_t* launches);
+/* The same record interval by interval, in the order the calls enqueued them: stage[i] is a
+ * MOE_STAGE_* id, ms[i] its elapsed time.  At most `capacity` intervals are returned (the rest
+ * are dropped); *count = number returned.  Waits for the events; clears the record. */
+moe_status moe_profile_read_intervals(moe_ctx* ctx, int32_t* stage, float* ms, int32_t capacity, int32_t* count);
+
+/* Measured ceiling of the matrix cores for the roofline report: one launch of a register-only loop
+ * of the MFMA instruction the grouped GEMMs use (1024 workgroups x 4 wavefronts x iters x 64
+ * instructions, no LDS or memory traffic inside the loop), timed with HIP events on hip_stream.
+ * The sustained rate depends on the operand values (the chip is power-limited on dense bf16
+ * work), so the operand fragments are read from a_bf16 / b_bf16 (device, `bytes` bytes each,
+ * 16-byte aligned; e.g. a packed weight matrix and the activations of the workload); NULL for
+ * both = all-zero operands.  sink: device scratch of at least 1 MiB (receives checksums).
+ * SYNCHRONISES the stream.  *tflops = 2*16*16*32 FLOP per instruction / elapsed time. */
+moe_status moe_profile_mfma_ceiling(moe_ctx* ctx, const void* a_bf16, const void* b_bf16, size_t bytes, int32_t iters,
+                                    void* sink, size_t sink_bytes, double* tflops, double* ms_or_null, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -21,9 +21,10 @@ STAGES = ["route", "permute_index", "permute_gather", "plan", "ffn_gate_up", "ff
 
 EXPORTS = [
     "moe_create", "moe_destroy", "moe_last_error", "moe_workspace_bytes", "moe_h_scratch_bytes", "moe_set_option", "moe_pack_weight",
+    "moe_gate_packed_bytes", "moe_pack_gate",
     "moe_route", "moe_permute", "moe_grouped_ffn", "moe_combine", "moe_layer", "moe_layer_static", "moe_layer_views",
     "moe_layer_streamed", "moe_stream_stats", "moe_estimate_streamed_ms", "moe_accumulate", "moe_layer_chunked",
-    "moe_profile_enable", "moe_profile_read",
+    "moe_profile_enable", "moe_profile_read", "moe_profile_read_intervals", "moe_profile_mfma_ceiling",
 ]
 
 
@@ -62,6 +63,9 @@ def load_library():
     lib.moe_workspace_bytes.restype = C.c_size_t
     lib.moe_h_scratch_bytes.argtypes = [sp]
     lib.moe_h_scratch_bytes.restype = C.c_size_t
+    lib.moe_gate_packed_bytes.argtypes = [sp]
+    lib.moe_gate_packed_bytes.restype = C.c_size_t
+    lib.moe_pack_gate.argtypes = [C.c_void_p, sp, vp, vp, vp]
     lib.moe_set_option.argtypes = [C.c_void_p, C.c_char_p, C.c_int32]
     lib.moe_pack_weight.argtypes = [C.c_void_p, vp, C.c_int32, C.c_int32, vp, vp]
     lib.moe_route.argtypes = [C.c_void_p, sp, vp, vp, f32p, i32p, f32p, f32p, vp, C.c_size_t, vp]
@@ -79,10 +83,14 @@ def load_library():
                                     C.POINTER(C.c_void_p)]
     lib.moe_profile_enable.argtypes = [C.c_void_p, C.c_int32]
     lib.moe_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
+    lib.moe_profile_read_intervals.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_float), C.c_int32,
+                                               C.POINTER(C.c_int32)]
+    lib.moe_profile_mfma_ceiling.argtypes = [C.c_void_p, vp, vp, C.c_size_t, C.c_int32, vp, C.c_size_t,
+                                             C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
     lib.moe_estimate_streamed_ms.argtypes = [sp, C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.c_double, C.c_double]
     lib.moe_estimate_streamed_ms.restype = C.c_double
     for name in EXPORTS:
-        if name not in ("moe_destroy", "moe_last_error", "moe_workspace_bytes", "moe_h_scratch_bytes",
+        if name not in ("moe_destroy", "moe_last_error", "moe_workspace_bytes", "moe_h_scratch_bytes", "moe_gate_packed_bytes",
                         "moe_estimate_streamed_ms"):
             getattr(lib, name).restype = C.c_int
     _lib = lib
@@ -176,6 +184,15 @@ class Moe:
         rows, cols = w.shape
         out = torch.empty(rows * cols, dtype=torch.bfloat16, device=w.device)
         self._check(self.lib.moe_pack_weight(self.h, _ptr(w), rows, cols, _ptr(out), _stream()))
+        return out
+
+    def pack_gate(self, shape, wg: torch.Tensor):
+        """Packed gate matrix for option "gate_packed" (None when the shape's router does not use one)."""
+        n = int(self.lib.moe_gate_packed_bytes(C.byref(shape)))
+        if n == 0:
+            return None
+        out = torch.empty(n // 2, dtype=torch.bfloat16, device=wg.device)
+        self._check(self.lib.moe_pack_gate(self.h, C.byref(shape), _ptr(wg), _ptr(out), _stream()))
         return out
 
     def pack_experts(self, w1: Sequence[torch.Tensor], w3: Sequence[torch.Tensor], w2: Sequence[torch.Tensor]):
@@ -273,6 +290,27 @@ class Moe:
     # ---- profiling ---------------------------------------------------------------------
     def profile_enable(self, on: bool):
         self._check(self.lib.moe_profile_enable(self.h, 1 if on else 0))
+
+    def profile_read_intervals(self, capacity: int = 8192):
+        """{stage name: [ms, ...]} of every interval recorded since the last read, in order."""
+        st = (C.c_int32 * capacity)()
+        ms = (C.c_float * capacity)()
+        n = C.c_int32()
+        self._check(self.lib.moe_profile_read_intervals(self.h, st, ms, capacity, C.byref(n)))
+        out = {s: [] for s in STAGES}
+        for i in range(n.value):
+            out[STAGES[st[i]]].append(float(ms[i]))
+        return out
+
+    def mfma_ceiling(self, a, b, iters: int, sink):
+        """One timed launch of the register-only MFMA loop; a, b: bf16 device tensors of equal size or None.
+        Returns (TFLOP/s, ms)."""
+        tf, ms = C.c_double(), C.c_double()
+        nbytes = 0 if a is None else min(a.numel() * a.element_size(), b.numel() * b.element_size())
+        self._check(self.lib.moe_profile_mfma_ceiling(self.h, _ptr(a), _ptr(b), nbytes, iters, _ptr(sink),
+                                                      sink.numel() * sink.element_size(), C.byref(tf), C.byref(ms),
+                                                      _stream()))
+        return tf.value, ms.value
 
     def profile_read(self):
         ms = (C.c_double * len(STAGES))()

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmoe_mi355.so")
-SOURCES = ["api.hip", "route.hip", "permute.hip", "ffn_gemm.hip", "combine.hip"]
+SOURCES = ["api.hip", "route.hip", "permute.hip", "ffn_gemm.hip", "combine.hip", "profile.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
          "-Wno-unknown-attributes"]

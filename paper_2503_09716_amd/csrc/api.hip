@@ -34,10 +34,11 @@ struct ProfRec {
 struct moe_ctx {
     int device = 0;
     char err[512] = {0};
-    GemmConfig gemm{1, 4, 0, 1, 1, 0, 0, -1, -1, 1, 0, -1};
+    GemmConfig gemm{1, 4, 0, 1, 1, 0, 0, -1, -1, 1, -1};
     bool y_fp32 = true;    // dtype of y_perm / y_shared in the staged calls
     int layer_y = -1;      // moe_layer's y_perm: 1 fp32, 0 bf16, -1 choose (its y_shared is always fp32)
     bool out_fp32 = false; // dtype of the layer output
+    bool gate_packed = false;  // E > 16: the wg argument is already in the packed layout (moe_pack_gate)
     char* static_ws = nullptr;  // this device's address of `scratch`
     // Ring of device pointer tables [3][MAX_GROUPS] (W1p, W3p, W2p), each with a pinned host
     // staging copy and an event marking the end of its upload.
@@ -130,7 +131,7 @@ int down_tail_splits(const moe_shape& s) {
 // Workspace layout: fixed order, every region 256-byte aligned.
 struct Layout {
     size_t topk_idx, topk_w, offsets, perm, inv_perm, row_token, chunk_counts, plan, descs_up, descs_down,
-        split_tails, split_partial, rt_plan, rt_table, rt_descs, rt_wg, rt_logits, x_tiled, h, y_perm, y_shared, total;
+        split_tails, split_partial, rt_wg, rt_logits, x_tiled, h, y_perm, y_shared, total;
 };
 
 Layout make_layout(const moe_shape& s) {
@@ -151,11 +152,8 @@ Layout make_layout(const moe_shape& s) {
     L.descs_down = take(((size_t)max_mtiles(s, 128) + (size_t)s.E * (dsp - 1)) * sizeof(TileDesc));
     L.split_tails = take((size_t)s.E * sizeof(SplitTail));
     L.split_partial = take(dsp > 1 ? (size_t)s.E * dsp * SPLIT_TAIL_ROWS * s.H * 4 : 0);
-    // router GEMM (E > 16): plan, W pointer per K-split, tile list, packed gate matrix, partial logits
+    // router GEMM (E > 16): packed gate matrix (unless the caller passes it packed), partial logits
     const RouteGemm rg = route_gemm_config(s);
-    L.rt_plan = take(rg.splits ? sizeof(PlanHeader) : 0);
-    L.rt_table = take(rg.splits ? 8 * sizeof(void*) : 0);
-    L.rt_descs = take(rg.splits ? (size_t)rg.splits * ((s.T + 127) / 128) * sizeof(TileDesc) : 0);
     L.rt_wg = take(rg.splits ? (size_t)rg.ep * s.H * 2 : 0);
     L.rt_logits = take(rg.splits ? (size_t)rg.splits * s.T * rg.ep * 4 : 0);
     L.x_tiled = take(((R + 15) & ~(size_t)15) * s.H * 2);
@@ -247,21 +245,25 @@ moe_status run_route(moe_ctx* c, const moe_shape& s, const void* x, const void* 
         return MOE_OK;
     }
     const Layout L = make_layout(s);
-    PlanHeader* plan = (PlanHeader*)(ws + L.rt_plan);
-    const void** table = (const void**)(ws + L.rt_table);
-    TileDesc* descs = (TileDesc*)(ws + L.rt_descs);
     const int k_split = s.H / rg.splits;
-    HIP_TRY(c, launch_pack_weight(wg, s.H, s.E, rg.ep, ws + L.rt_wg, st));
-    HIP_TRY(c, launch_route_plan(s.T, rg.tm, rg.splits, ws + L.rt_wg, k_split / 32, plan, descs, table, st));
+    // The gate matrix is static: a caller that packs it once (moe_pack_gate, option "gate_packed")
+    // spares every call this launch.
+    const char* wg_packed = (const char*)wg;
+    if (!c->gate_packed) {
+        HIP_TRY(c, launch_pack_weight(wg, s.H, s.E, rg.ep, ws + L.rt_wg, st));
+        wg_packed = ws + L.rt_wg;
+    }
     GemmArgs a;
     memset(&a, 0, sizeof(a));
     a.a_routed = (const char*)x;
     a.a_shared = (const char*)x;
-    a.w_a = (const void* const*)table;
+    a.w_uniform = wg_packed;
+    a.w_uniform_stride = (uint32_t)(k_split / 32) * 1024u;   // K-split s starts s * (k_split / 32) blocks of 1 KiB along
+    a.uniform_tm = rg.tm;
+    a.uniform_per = (s.T + rg.tm - 1) / rg.tm;
+    a.uniform_splits = rg.splits;
     a.out_routed = ws + L.rt_logits;
     a.out_shared = ws + L.rt_logits;
-    a.descs = descs;
-    a.plan = plan;
     a.K = k_split;
     a.N = rg.ep;
     a.T = s.T;
@@ -272,7 +274,6 @@ moe_status run_route(moe_ctx* c, const moe_shape& s, const void* x, const void* 
     a.xcd_remap = 0;
     a.small_tiles = 1;
     a.out_fp32 = 3;
-    a.k_step_on = 1;
     a.lda_bytes = s.H * 2;
     a.kt_w = s.H / 32;
     a.split_rows = s.T;
@@ -377,7 +378,6 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     a.xcd_remap = c->gemm.xcd_remap;
     a.small_tiles = c->gemm.small_tiles;
     a.out_fp32 = 0;
-    a.k_step_on = c->gemm.probe_k_resident ? 0 : 1;
     a.t_pad = (s.T + 15) & ~15;
     a.split_rows = 0;
     // GEMM 1: [rows, H] x W1p/W3p [F, H] -> h [rows, F]
@@ -581,11 +581,11 @@ moe_status moe_set_option(moe_ctx* c, const char* key, int32_t v) {
     if (!strcmp(key, "x_tiled") && v >= -1 && v <= 1) { c->gemm.x_tiled = v; return MOE_OK; }
     if (!strcmp(key, "down_tail_splits") && (v == 0 || v == 1)) { c->gemm.down_tail_splits = v; return MOE_OK; }
     if (!strcmp(key, "tails_last") && v >= -1 && v <= 1) { c->gemm.tails_last = v; return MOE_OK; }
-    if (!strcmp(key, "probe_k_resident") && (v == 0 || v == 1)) { c->gemm.probe_k_resident = v; return MOE_OK; }
     if (!strcmp(key, "tall_tiles") && v >= -1 && v <= 2) { c->gemm.tall_tiles = v; return MOE_OK; }
     if (!strcmp(key, "y_fp32") && (v == 0 || v == 1)) { c->y_fp32 = v != 0; return MOE_OK; }
     if (!strcmp(key, "layer_y_fp32") && v >= -1 && v <= 1) { c->layer_y = v; return MOE_OK; }
     if (!strcmp(key, "out_fp32") && (v == 0 || v == 1)) { c->out_fp32 = v != 0; return MOE_OK; }
+    if (!strcmp(key, "gate_packed") && (v == 0 || v == 1)) { c->gate_packed = v != 0; return MOE_OK; }
     return fail(c, MOE_E_ARG, "unknown option or value out of range: %s=%d", key, (int)v);
 }
 
@@ -597,6 +597,22 @@ moe_status moe_pack_weight(moe_ctx* c, const void* w, int32_t rows, int32_t cols
     if ((int64_t)rows * cols * 2 >= ((int64_t)1 << 32)) return fail(c, MOE_E_UNSUPPORTED, "pack: matrix reaches 4 GiB");
     HIP_TRY(c, hipSetDevice(c->device));
     HIP_TRY(c, launch_pack_weight(w, rows, cols, cols, packed, (hipStream_t)stream));
+    return MOE_OK;
+}
+
+size_t moe_gate_packed_bytes(const moe_shape* s) {
+    moe_status st;
+    if (shape_problem(s, &st)) return 0;
+    const RouteGemm rg = route_gemm_config(*s);
+    return rg.splits ? (size_t)rg.ep * s->H * 2 : 0;
+}
+
+moe_status moe_pack_gate(moe_ctx* c, const moe_shape* s, const void* wg, void* wg_packed, void* stream) {
+    if (moe_status st = check_common(c, s)) return st;
+    const RouteGemm rg = route_gemm_config(*s);
+    if (!rg.splits) return fail(c, MOE_E_ARG, "pack_gate: with E <= 16 the router reads the gate matrix as it is");
+    if (!wg || !wg_packed || wg == wg_packed) return fail(c, MOE_E_ARG, "pack_gate: NULL or aliased buffers");
+    HIP_TRY(c, launch_pack_weight(wg, s->H, s->E, rg.ep, wg_packed, (hipStream_t)stream));
     return MOE_OK;
 }
 
@@ -873,6 +889,48 @@ moe_status moe_layer_views(const moe_shape* s, void* ws, int32_t** idx, float** 
 moe_status moe_profile_enable(moe_ctx* c, int32_t on) {
     if (!c) return MOE_E_ARG;
     c->prof = on != 0;
+    return MOE_OK;
+}
+
+moe_status moe_profile_read_intervals(moe_ctx* c, int32_t* stage, float* ms, int32_t capacity, int32_t* count) {
+    if (!c || !stage || !ms || !count || capacity < 0) return MOE_E_ARG;
+    c->err[0] = 0;
+    int n = 0;
+    for (auto& r : c->recs) {
+        HIP_TRY(c, hipEventSynchronize(r.b));
+        float v = 0.f;
+        HIP_TRY(c, hipEventElapsedTime(&v, r.a, r.b));
+        if (n < capacity) { stage[n] = r.stage; ms[n] = v; ++n; }
+        c->pool.push_back(r.a);
+        c->pool.push_back(r.b);
+    }
+    c->recs.clear();
+    *count = n;
+    return MOE_OK;
+}
+
+moe_status moe_profile_mfma_ceiling(moe_ctx* c, const void* a, const void* b, size_t bytes, int32_t iters, void* sink,
+                                    size_t sink_bytes, double* tflops, double* ms_out, void* stream) {
+    if (!c) return MOE_E_ARG;
+    c->err[0] = 0;
+    if (!sink || !tflops || iters < 1 || iters > (1 << 22)) return fail(c, MOE_E_ARG, "mfma_ceiling: bad argument");
+    if ((a || b) && (bytes < 16 || bytes >= ((size_t)1 << 35))) return fail(c, MOE_E_ARG, "mfma_ceiling: operand buffers need 16 bytes .. 32 GiB");
+    if (((uintptr_t)a | (uintptr_t)b) & 15) return fail(c, MOE_E_ARG, "mfma_ceiling: operand buffers must be 16-byte aligned");
+    if (sink_bytes < (size_t)CEILING_BLOCKS * 256 * sizeof(float)) return fail(c, MOE_E_WORKSPACE, "mfma_ceiling: sink needs %zu bytes", (size_t)CEILING_BLOCKS * 256 * sizeof(float));
+    HIP_TRY(c, hipSetDevice(c->device));
+    hipStream_t hs = (hipStream_t)stream;
+    hipEvent_t e0 = get_event(c), e1 = get_event(c);
+    if (!e0 || !e1) return fail(c, MOE_E_HIP, "mfma_ceiling: no event");
+    HIP_TRY(c, hipEventRecord(e0, hs));
+    HIP_TRY(c, launch_mfma_ceiling(a, b, bytes, CEILING_BLOCKS, iters, (float*)sink, hs));
+    HIP_TRY(c, hipEventRecord(e1, hs));
+    HIP_TRY(c, hipEventSynchronize(e1));
+    float ms = 0.f;
+    HIP_TRY(c, hipEventElapsedTime(&ms, e0, e1));
+    c->pool.push_back(e0);
+    c->pool.push_back(e1);
+    *tflops = mfma_ceiling_flops(CEILING_BLOCKS, iters) / ((double)ms * 1e-3) / 1e12;
+    if (ms_out) *ms_out = ms;
     return MOE_OK;
 }
 

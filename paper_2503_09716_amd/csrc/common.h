@@ -20,7 +20,7 @@ __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_
 //   router GEMM  : group = K-split index s, row0 = first token, srow = -1 - s
 //   shared group : group = E + s,     row0 = first token,  srow = s * t_pad (row offset inside the shared region of h)
 //   K-split piece of a short tail of the down GEMM: group = expert id, row0 = permuted row,
-//                  srow = -1 - (q * splits + s) for piece s of the q-th split tail
+//                  srow = -2 - (q * splits + s) for piece s of the q-th split tail
 struct TileDesc {
     int32_t group;
     int32_t row0;
@@ -62,7 +62,6 @@ struct GemmArgs {
     int32_t xcd_remap;
     int32_t small_tiles;       // 1: a short tail tile runs the 128/64/32-row variant
     int32_t out_fp32;          // GEMM2: output stored as fp32 (else bf16): bit 0 routed tiles, bit 1 shared tiles (GEMM1 always stores bf16)
-    int32_t k_step_on;         // 1: K offsets advance per sub-tile; 0 only for the cache-resident timing probe
     int32_t lda_bytes;         // row stride of a row-major A operand
     int32_t kt_w;              // 1 KiB blocks per 16-row group of the packed W (its full K / 32)
     int32_t split_rows;        // router GEMM: output rows per K-split (partial s is written at rows s*split_rows + ...)
@@ -71,6 +70,11 @@ struct GemmArgs {
     char* out_partial;         // down GEMM: fp32 partial results of split tails, SPLIT_TAIL_ROWS rows per piece
     int32_t a_tiled;           // A operand is in 16 x 32 blocks (else row-major): bit 0 routed tiles, bit 1 shared tiles
     int32_t t_pad;             // T rounded up to 16: rows of one shared expert's block of h
+    // Router GEMM (w_uniform != nullptr): no tile list and no pointer table; K-split s multiplies the
+    // packed gate matrix from byte w_uniform_stride * s on, over uniform_per tiles of uniform_tm rows.
+    const char* w_uniform;
+    uint32_t w_uniform_stride;
+    int32_t uniform_tm, uniform_per, uniform_splits;
 };
 
 struct GemmConfig {
@@ -84,7 +88,6 @@ struct GemmConfig {
     int x_tiled;           // moe_layer: 1 = gather x into a tiled x_perm first, 0 = gather inside GEMM 1, -1 = choose
     int tails_last;        // order of the m-tile lists: 1 = short tail tiles after all full tiles, 0 = in group order, -1 = choose
     int down_tail_splits;  // 1: the down GEMM cuts the K range of short tail tiles into pieces (few experts only); 0: off
-    int probe_k_resident;  // timing probe: every K step re-reads the first tile (results are meaningless)
     int tall_tiles;        // a tail of <= 64 rows joins its group's last full 256-row tile (4 waves x 1 wave row only):
                            // 0 off, 1 tall tiles after the run region, 2 in place, -1 choose
 };
@@ -98,9 +101,6 @@ inline int64_t max_mtiles(const moe_shape& s, int tm) {
 // ---- launchers (each only enqueues on `st`; returns the launch status) ----
 hipError_t launch_route(const moe_shape& s, const void* x, const void* wg, const float* bias, int32_t* idx,
                         float* w, float* logits, hipStream_t st);   // E <= 16: one streaming kernel
-// E > 16: uniform tile list for the router GEMM (splits x tiles of tm tokens) + the W pointer per split
-hipError_t launch_route_plan(int T, int tm, int splits, const void* wg_packed, int kt_split, PlanHeader* plan,
-                             TileDesc* descs, const void** table, hipStream_t st);
 // softmax + top-k from `splits` fp32 partial logit matrices [splits][T][ep]
 hipError_t launch_route_topk(const moe_shape& s, const float* partial, int splits, int ep, const float* bias,
                              int32_t* idx, float* w, float* logits, hipStream_t st);
@@ -131,6 +131,11 @@ hipError_t launch_combine(const moe_shape& s, const void* y_perm, const int32_t*
                           const void* y_shared, void* out, bool y_fp32, bool shared_fp32, bool out_fp32, hipStream_t st);
 // in: logical [rows = K, cols] row-major; out: packed [cols_padded x K] (cols_padded % 32 == 0, columns >= cols are zero)
 hipError_t launch_pack_weight(const void* in, int rows, int cols, int cols_padded, void* out, hipStream_t st);
+
+// register-only MFMA loop (profile.hip): sink holds blocks*256 floats
+constexpr int CEILING_BLOCKS = 1024;
+double mfma_ceiling_flops(int blocks, int iters);
+hipError_t launch_mfma_ceiling(const void* a, const void* b, size_t bytes, int blocks, int iters, float* sink, hipStream_t st);
 
 // Rows of the h scratch: routed rows and each shared expert's rows start on a 16-row block boundary.
 inline int64_t h_rows(const moe_shape& s) {

@@ -145,7 +145,7 @@ __device__ __forceinline__ void ring_sync() {
 }
 
 // NW wavefronts as a WM x (NW/WM) grid; TI = 32-row X blocks per wave; GATED = GEMM 1.
-template <int NW, int WM, int TI, bool GATED>
+template <int NW, int WM, int TI, bool GATED, bool UNIFORM = false>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, const int n_tile, char* lds) {
     constexpr int WN = NW / WM;
     constexpr int TJ = 8 / WN;               // 32-row W blocks per wave
@@ -186,11 +186,11 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
     const int nseg = (!GATED && shared) ? p.nseg_shared : 1;
     const int KT = (tail_split ? K / p.tail_splits : K) / BK;   // sub-tiles per segment (>= 2)
     // K step in bytes: one 1 KiB block for tiled operands, 64 bytes along a row for row-major x
-    const int kstep_w = p.k_step_on ? 1024 : 0;
+    constexpr int kstep_w = 1024;
     // A operand layout (bit 0: routed tiles, bit 1: shared tiles): h is tiled; x is row-major
     // (read through the gather, by shared experts and by the router) unless a tiled x_perm exists
     const bool a_tiled = ((shared ? p.a_tiled >> 1 : p.a_tiled) & 1) != 0;
-    const int kstep_x = p.k_step_on ? (a_tiled ? 1024 : ROWB) : 0;
+    const int kstep_x = a_tiled ? 1024 : ROWB;
     const char* const a_base = shared ? p.a_shared : p.a_routed;
     const size_t a_seg_stride = (size_t)p.t_pad * (size_t)K * 2;   // one shared expert's block of h
 
@@ -329,7 +329,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
         // 1 KiB in a tiled operand (the packed W is always tiled)
         const size_t piece_shift = (size_t)split * (size_t)KT * 1024;
         rs_x = uniform_rsrc(a_base + (size_t)seg * a_seg_stride + (tail_split ? piece_shift : (size_t)split * (size_t)K * 2));
-        rs_w = uniform_rsrc((const char*)p.w_a[d.group + seg] + (tail_split ? piece_shift : 0));
+        // UNIFORM (router GEMM): one packed matrix, K-split s starts s * w_uniform_stride bytes along
+        if (UNIFORM) rs_w = uniform_rsrc(p.w_uniform + (size_t)d.group * (size_t)p.w_uniform_stride);
+        else rs_w = uniform_rsrc((const char*)p.w_a[d.group + seg] + (tail_split ? piece_shift : 0));
         if (GATED) rs_u = uniform_rsrc(p.w_b[d.group]);
         koff_x = 0;
         koff_w = 0;
@@ -489,7 +491,21 @@ __device__ __forceinline__ int tile_order(const int wg, const int total, const i
 // group) and X panels (same m) in L2.  (Runs of a fixed length that cross group boundaries
 // measured 5-12 % faster than runs fitted to each group.)  Entries past n_run are tail tiles
 // of different groups: they are walked along n, which shares the X panel.
+template <bool UNIFORM = false>
 __device__ __forceinline__ bool pick_tile(const GemmArgs& p, const bool gated, TileDesc& d, int& n_tile) {
+    if (UNIFORM) {
+        // Router GEMM: every K-split s covers all T rows in tiles of uniform_tm rows; nothing to look up.
+        const int L = blockIdx.x;
+        const int mt = L / p.n_tiles;
+        n_tile = L - mt * p.n_tiles;
+        if (mt >= p.uniform_per * p.uniform_splits) return false;
+        const int s = mt / p.uniform_per, m = mt - s * p.uniform_per;
+        d.group = s;
+        d.row0 = m * p.uniform_tm;
+        d.nrows = min(p.uniform_tm, p.T - d.row0);
+        d.srow = -1 - s;
+        return true;
+    }
     const int L = tile_order(blockIdx.x, gridDim.x, p.xcd_remap);
     const int count = gated ? p.plan->n_gate_up : p.plan->n_down;
     const int n_run = gated ? p.plan->n_run_up : p.plan->n_run_down;
@@ -514,18 +530,18 @@ __device__ __forceinline__ bool pick_tile(const GemmArgs& p, const bool gated, T
 }
 
 // 4 wavefronts (one per SIMD, up to 512 registers each), wave grid WM x 4/WM.
-template <int WM, bool GATED>
+template <int WM, bool GATED, bool UNIFORM = false>
 __global__ __launch_bounds__(256, 1) void ffn_gemm_kernel(const GemmArgs p) {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     TileDesc d;
     int n_tile;
-    if (!pick_tile(p, GATED, d, n_tile)) return;
+    if (!pick_tile<UNIFORM>(p, GATED, d, n_tile)) return;
     // 32-row blocks that hold real rows; 9 or 10: a tall tile (the plan kernel makes them for this wave grid only)
     const int blocks = d.nrows > 256 ? (d.nrows + 31) >> 5 : (p.small_tiles ? (d.nrows + 31) >> 5 : 8);
     if (WM == 2) {
-        if (blocks > 4) gemm_tile<4, 2, 4, GATED>(p, d, n_tile, lds);
-        else if (blocks > 2) gemm_tile<4, 2, 2, GATED>(p, d, n_tile, lds);
-        else gemm_tile<4, 2, 1, GATED>(p, d, n_tile, lds);
+        if (blocks > 4) gemm_tile<4, 2, 4, GATED, UNIFORM>(p, d, n_tile, lds);
+        else if (blocks > 2) gemm_tile<4, 2, 2, GATED, UNIFORM>(p, d, n_tile, lds);
+        else gemm_tile<4, 2, 1, GATED, UNIFORM>(p, d, n_tile, lds);
     } else {
         if (blocks > 9) gemm_tile<4, 1, 10, GATED>(p, d, n_tile, lds);
         else if (blocks > 8) gemm_tile<4, 1, 9, GATED>(p, d, n_tile, lds);
@@ -746,6 +762,7 @@ hipError_t ffn_gemm_init() {
     if (e != hipSuccess) return e;
     SET_LDS((ffn_gemm_kernel<2, true>))
     SET_LDS((ffn_gemm_kernel<2, false>))
+    SET_LDS((ffn_gemm_kernel<2, false, true>))
     SET_LDS((ffn_gemm_kernel<1, true>))
     SET_LDS((ffn_gemm_kernel<1, false>))
     SET_LDS((ffn_gemm_kernel8<2, true>))
@@ -769,6 +786,10 @@ hipError_t launch_ffn_plan(const moe_shape& s, const int32_t* offsets, int tm_up
 hipError_t launch_ffn_gemm(bool gated, const GemmArgs& a, const GemmConfig& cfg, hipStream_t st) {
     const dim3 grid((unsigned)(a.max_mtiles * a.n_tiles));
 #define LAUNCH(KERNEL, THREADS) hipLaunchKernelGGL((KERNEL), grid, dim3(THREADS), MAX_LDS, st, a)
+    if (a.w_uniform) {   // router GEMM: 4 waves as 2 x 2, tiles by arithmetic
+        LAUNCH((ffn_gemm_kernel<2, false, true>), 256);
+        return hipGetLastError();
+    }
     if (cfg.waves == 8) {
         if (cfg.wave_rows == 4) {
             if (gated) LAUNCH((ffn_gemm_kernel8<4, true>), 512);

@@ -116,6 +116,85 @@ __global__ __launch_bounds__(64) void permute_place_kernel(const int32_t* __rest
     }
 }
 
+// All three steps in ONE launch, for small batches (T*k <= FUSED_MAX_PAIRS), where two extra
+// launches cost more than the work (256 tokens top-2: 6 us against 13; from a few thousand pairs
+// on, the three kernels win: every workgroup here reads the whole index array): every workgroup
+// (one per chunk, 4 wavefronts) histograms ALL pairs into wave-private LDS counters, once counting everything (-> expert_offsets, the same in
+// every workgroup) and once counting only the chunks before its own (-> its cursors), then
+// places its chunk: wavefront w takes tokens 64w .. 64w+63 of the chunk, the lane masks of all
+// four wavefronts give a pair its rank.  Same result as the three kernels above, bit for bit,
+// without their two extra launches.
+constexpr int FUSED_MAX_PAIRS = 1 << 12;
+static_assert(PERMUTE_CHUNK_TOKENS == 256, "the fused kernel gives each of its 4 wavefronts 64 tokens of a chunk");
+
+__global__ __launch_bounds__(256) void permute_index_fused_kernel(const int32_t* __restrict__ idx, int T, int k, int E,
+                                                                  int32_t* __restrict__ offsets, int32_t* __restrict__ perm,
+                                                                  int32_t* __restrict__ inv_perm, int32_t* __restrict__ row_token) {
+    __shared__ int hist[4][2][MAX_E];              // [wave][0: all chunks, 1: chunks before mine][expert]
+    __shared__ unsigned long long mask[4][MAX_E];  // [wave][expert]: lanes of that wave that picked the expert
+    __shared__ int cur[MAX_E];
+    __shared__ int wave_sum[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, chunk = blockIdx.x;
+    for (int i = tid; i < 4 * 2 * MAX_E; i += 256) (&hist[0][0][0])[i] = 0;
+    for (int i = tid; i < 4 * MAX_E; i += 256) (&mask[0][0])[i] = 0ull;
+    __syncthreads();
+    const int n = T * k;
+    const int mine_begin = chunk * PERMUTE_CHUNK_TOKENS * k;   // pairs of earlier chunks come before this index
+    for (int i = tid; i < n; i += 256) {
+        const int e = idx[i];
+        if ((unsigned)e < (unsigned)E) {
+            atomicAdd(&hist[wave][0][e], 1);                   // integer LDS counters: order-independent
+            if (i < mine_begin) atomicAdd(&hist[wave][1][e], 1);
+        }
+    }
+    __syncthreads();
+    // thread e: totals of expert e, then an exclusive prefix sum over the experts (E <= 256 = one per thread)
+    int total = 0, before = 0;
+    if (tid < E) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) { total += hist[w][0][tid]; before += hist[w][1][tid]; }
+    }
+    int incl = total;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int t = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += t;
+    }
+    if (lane == 63) wave_sum[wave] = incl;
+    __syncthreads();
+    int base = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+        if (w < wave) base += wave_sum[w];
+    const int excl = base + incl - total;
+    if (tid < E) {
+        cur[tid] = excl + before;
+        if (chunk == 0) offsets[tid] = excl;
+    }
+    if (chunk == 0 && tid == E - 1) offsets[E] = excl + total;
+    // placement of this chunk: wave w owns tokens 64w .. 64w+63
+    const int t = chunk * PERMUTE_CHUNK_TOKENS + tid;
+    const bool valid = t < T;
+    const int32_t* mine = idx + (size_t)t * k;
+    const unsigned long long bit = 1ull << lane, lt = bit - 1ull;
+    if (valid)
+        for (int j = 0; j < k; ++j) {
+            const int e = mine[j];
+            if ((unsigned)e < (unsigned)E) atomicOr(&mask[wave][e], bit);
+        }
+    __syncthreads();
+    if (valid)
+        for (int j = 0; j < k; ++j) {
+            const int e = mine[j];
+            if ((unsigned)e >= (unsigned)E) continue;
+            int slot = cur[e] + __popcll(mask[wave][e] & lt);
+            for (int w = 0; w < wave; ++w) slot += __popcll(mask[w][e]);
+            perm[slot] = t * k + j;
+            inv_perm[(size_t)t * k + j] = slot;
+            if (row_token) row_token[slot] = t;
+        }
+}
+
 // One wavefront copies one row per pass; 16 bytes per lane, consecutive lanes consecutive addresses.
 __global__ __launch_bounds__(256) void permute_gather_kernel(const uint4* __restrict__ x, const int32_t* __restrict__ perm,
                                                              int R, int k, int row16, uint4* __restrict__ x_perm) {
@@ -166,6 +245,11 @@ hipError_t launch_permute_gather_tiled(const moe_shape& s, const void* x, const 
 hipError_t launch_permute_index(const moe_shape& s, const int32_t* idx, int32_t* chunk_counts, int32_t* offsets,
                                 int32_t* perm, int32_t* inv_perm, int32_t* row_token, hipStream_t st) {
     const int nchunks = permute_chunks(s);
+    if ((int64_t)s.T * s.top_k <= FUSED_MAX_PAIRS) {
+        hipLaunchKernelGGL(permute_index_fused_kernel, dim3(nchunks), dim3(256), 0, st, idx, s.T, s.top_k, s.E, offsets, perm,
+                           inv_perm, row_token);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(permute_count_kernel, dim3(nchunks), dim3(64), 0, st, idx, s.T, s.top_k, s.E, chunk_counts);
     hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(256), 0, st, chunk_counts, nchunks, s.E, offsets);
     hipLaunchKernelGGL(permute_place_kernel, dim3(nchunks), dim3(64), 0, st, idx, s.T, s.top_k, s.E,

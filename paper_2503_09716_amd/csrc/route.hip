@@ -250,38 +250,7 @@ __global__ __launch_bounds__(256) void route_topk_kernel(const float* __restrict
     route_finish<NV>(v, lane, t, E, k, renorm, scale, idx_out, w_out, logits_out);
 }
 
-// Tile list of the router GEMM: for every K-split s, ceil(T/tm) tiles of tm tokens; table[s]
-// points at the K-range of the packed gate matrix that split s multiplies.
-__global__ __launch_bounds__(256) void route_plan_kernel(int T, int tm, int splits, const char* wg_packed, int kt_split,
-                                                         PlanHeader* plan, TileDesc* descs, const void** table) {
-    const int per = (T + tm - 1) / tm;
-    for (int i = threadIdx.x; i < per * splits; i += 256) {
-        const int s = i / per, m = i - s * per;
-        TileDesc d;
-        d.group = s;
-        d.row0 = m * tm;
-        d.nrows = min(tm, T - m * tm);
-        d.srow = -1 - s;
-        descs[i] = d;
-    }
-    if (threadIdx.x < splits) table[threadIdx.x] = wg_packed + (size_t)threadIdx.x * kt_split * 1024;
-    if (threadIdx.x == 0) {
-        plan->n_gate_up = 0;
-        plan->n_down = per * splits;
-        plan->n_run_up = 0;
-        plan->n_run_down = per * splits;
-        plan->n_split_tails = 0;
-    }
-}
-
 }  // namespace
-
-hipError_t launch_route_plan(int T, int tm, int splits, const void* wg_packed, int kt_split, PlanHeader* plan,
-                             TileDesc* descs, const void** table, hipStream_t st) {
-    hipLaunchKernelGGL(route_plan_kernel, dim3(1), dim3(256), 0, st, T, tm, splits, (const char*)wg_packed, kt_split,
-                       plan, descs, table);
-    return hipGetLastError();
-}
 
 hipError_t launch_route_topk(const moe_shape& s, const float* partial, int splits, int ep, const float* bias,
                              int32_t* idx, float* w, float* logits, hipStream_t st) {
