@@ -240,7 +240,7 @@ def hbm_stages(moe, L: Layer, copy_gbs: float, reps: int = 5):
     res["permute"] = entry((T + R) * H * 2 + 16 * R, t, n, {"what": "moe_permute: histogram + scan + placement + row gather"})
     del xs, xp
     # combine, for both dtypes of y_perm
-    layer_y32 = not (k >= 4 and Ns > 0)
+    layer_y32 = not (k >= 4 and Ns > 0)   # moe_layer's rule (option "layer_y_fp32" = -1)
     for y32 in (True, False):
         ysz = 4 if y32 else 2
         ydt = torch.float32 if y32 else torch.bfloat16

@@ -482,7 +482,10 @@ moe_status run_front(moe_ctx* c, const moe_shape& s, const void* x, const void* 
     // output: at least 4 routed terms next to shared experts of weight 1, which then carry most
     // of the output (measured at full size: no change of the error).  Without shared experts the
     // routed terms are the whole output and their rounding would use up most of the error bar
-    // whatever their weights: fp32 there.  y_shared (weight 1) is always fp32.
+    // whatever their weights: fp32 there (measured on the Mixtral-shaped workloads against the
+    // oracle, every token: bf16 y_perm would take 1 % off the step and move the worst element
+    // from 1.04e-2 to 1.97e-2 x RMS on the 8x7B shape and to 2.1e-2, past the bar, on the 8x22B shape).
+    // y_shared (weight 1) is always fp32.
     f->y32 = c->layer_y >= 0 ? c->layer_y != 0 : !(s.top_k >= 4 && s.num_shared > 0);
     return MOE_OK;
 }
