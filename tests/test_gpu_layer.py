@@ -162,6 +162,54 @@ def test_layer_metamorphic_exact(moe):
 
 
 # nsample = 0: every token goes through the oracle
+def test_layer_hand_placed_extreme_inputs(moe):
+    """The generator's values stop at 4.3 sigma; here hand-placed ones: rows of -0.0 and of mixed +-0,
+    bf16 denormals, elements of +-2^12 among ordinary ones, a whole row of large values, and weights
+    with a few entries 100 x the usual scale.  Routing (exact ties included: an all-zero row must pick
+    experts 0..k-1) against the oracle, and the output of EVERY token held to the bar relative to
+    that token's own RMS (a single bar over the whole output would be set by the huge rows alone)."""
+    cfg = scaled_config("C4", T=200, H=256, F=192, E=24, top_k=4, num_shared=1)
+    li = make_layer_inputs(cfg, device="cuda")
+    x = li.x.clone()
+    neg0 = torch.tensor(-0.0, dtype=torch.bfloat16)
+    x[3, :] = neg0                                              # a row of -0.0
+    x[4, 0::2] = 0.0; x[4, 1::2] = neg0                         # +-0 mixed
+    den = torch.from_numpy(np.array([1, 0x8001, 0x007F, 0x807F], np.uint16).view(np.int16)).view(torch.bfloat16).cuda()   # smallest / largest bf16 denormals
+    x[5, :] = den.repeat(cfg.H // 4)                            # a row of denormals
+    x[6, 10:14] = den                                           # denormals among ordinary values
+    x[7, 17] = 4096.0; x[7, 200] = -4096.0                      # two huge elements in an ordinary row
+    x[8, :] = x[8, :] * 512                                     # a whole row 512 x larger
+    x[9, :] = 0.0; x[9, 5] = 1.0                                # one-hot row
+    li.x = x
+    li.w1[2][7, :] = li.w1[2][7, :] * 100                       # weight rows / entries 100 x the usual scale
+    li.w3[5][:, 11] = li.w3[5][:, 11] * 100
+    li.w2[cfg.E][3, 9] = 2.0                                    # in the shared expert too
+    say("extreme", cfg)
+    gl = P.GpuLayer(moe, li)
+    out, out16 = gl.run_layer_both()
+    assert torch.isfinite(out).all()
+    views = moe.layer_views(gl.shape, gl.ws)
+    idx = views["topk_idx"].cpu().numpy(); w = views["topk_w"].cpu().numpy()
+    ref_r = gl.oracle_route()
+    say(P.compare_routing(idx, w, ref_r, cfg.top_k, cfg.renormalize, cfg.routed_scale))
+    for t in (3, 4):                                           # all logits equal: lowest expert ids, in order, equal weights
+        assert idx[t].tolist() == list(range(cfg.top_k))
+        np.testing.assert_allclose(w[t], 1.0 / cfg.E, rtol=1e-6)
+    ref = gl.oracle_layer(idx, w)
+    got = out.cpu().numpy()
+    assert (got[3] == 0).all() and (got[4] == 0).all() and (ref[3] == 0).all()
+    tok_rms = np.sqrt((ref.astype(np.float64) ** 2).mean(axis=1))
+    err = np.abs(got.astype(np.float64) - ref).max(axis=1)
+    live = tok_rms > 1e-30
+    worst = (err[live] / tok_rms[live]).max()
+    say("worst token: max-abs error %.4g x its own RMS; RMS range %.3g .. %.3g" % (worst, tok_rms[live].min(), tok_rms[live].max()))
+    # per-token bar: the bf16 rounding of h alone is up to 2^-9 of each term, and a token's own RMS is a
+    # smaller yardstick than the RMS over many tokens, so allow twice the layer-level bar
+    assert worst <= 2 * P.OUT_BAR
+    # denormal rows: the matrix cores may flush bf16 denormals, the oracle does not; both are ~1e-40 from zero
+    assert np.abs(got[5]).max() < 1e-30 and np.abs(ref[5]).max() < 1e-30
+
+
 FULL = [("C2", 0), ("C3", 512), ("C4", 0), ("C5", 1024), ("C5b", 512)]
 
 
