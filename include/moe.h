@@ -23,7 +23,12 @@
  *    MOE_E_ARG / MOE_E_UNSUPPORTED / MOE_E_WORKSPACE.  moe_last_error gives the message.
  *  - Expert weight tables are HOST arrays of DEVICE pointers, read when the call is made,
  *    so that a weight streamer may repoint them between calls (sequential execution of
- *    experts with prefetched weights, Sec. 4.2).
+ *    experts with prefetched weights, Sec. 4.2).  The library copies them into one of 8
+ *    device tables the context owns and re-uses the last copy while the pointers stay the same
+ *    (a call on another stream first waits for that copy).  A HIP graph captured from a call
+ *    refers to the table that was current at capture: it stays valid until 8 further tables
+ *    have been uploaded on the context (calls with other weight pointers; every expert group of
+ *    moe_layer_streamed is one), so give graphs that are replayed for long a context of their own.
  *  - Weight layout on the hot path is the PACKED one produced by moe_pack_weight from the
  *    logical [H,F] / [F,H] matrices (same number of bytes): the transposed matrix W[n][k]
  *    (k = contraction index) is cut into blocks of 16 rows x 32 k = 1 KiB, blocks ordered

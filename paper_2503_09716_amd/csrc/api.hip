@@ -48,6 +48,7 @@ struct moe_ctx {
     int tab_next = 0;
     int tab_cur = -1;
     int tab_n = 0;
+    hipStream_t tab_stream = nullptr;     // stream of the current table's upload
     std::vector<const void*> tab_shadow;  // contents of slot tab_cur
     // streamed weights: copy stream, slot hand-over events, pinned copy of expert_offsets, counters
     hipStream_t copy_stream = nullptr;
@@ -232,6 +233,10 @@ moe_status weight_table(moe_ctx* c, int n, const void* const* w1, const void* co
         HIP_TRY(c, hipEventRecord(c->tab_done[slot], st));
         c->tab_cur = slot;
         c->tab_n = n;
+        c->tab_stream = st;
+    } else if (st != c->tab_stream) {
+        // the cached table was uploaded on another stream: this stream's kernels must not overtake that copy
+        HIP_TRY(c, hipStreamWaitEvent(st, c->tab_done[c->tab_cur], 0));
     }
     *out = c->d_tab[c->tab_cur];
     return MOE_OK;
