@@ -156,7 +156,7 @@ class GpuLayer:
 
 
 def check_layer_against_oracle(gl: GpuLayer, out: torch.Tensor, tokens=None, check_all_routing: bool = True,
-                               out16: torch.Tensor = None):
+                               out16: torch.Tensor = None, progress=None):
     """Full check of one moe_layer result.  tokens=None: every token through the oracle;
     otherwise the FFN/combine part only for the listed tokens (routing still for all tokens
     when check_all_routing)."""
@@ -183,7 +183,15 @@ def check_layer_against_oracle(gl: GpuLayer, out: torch.Tensor, tokens=None, che
     if tokens is None:
         tokens = np.arange(cfg.T, dtype=np.int32)
     tokens = np.asarray(tokens, dtype=np.int32)
-    out_ref = gl.oracle_layer(idx[tokens], w[tokens], tokens=tokens)
+    if progress is None:
+        out_ref = gl.oracle_layer(idx[tokens], w[tokens], tokens=tokens)
+    else:       # long runs: the oracle in pieces, a line after each, so that the run is seen to be alive
+        parts = []
+        for lo in range(0, len(tokens), 1024):
+            tk = tokens[lo:lo + 1024]
+            parts.append(gl.oracle_layer(idx[tk], w[tk], tokens=tk))
+            progress("  oracle: %d of %d tokens" % (min(lo + 1024, len(tokens)), len(tokens)))
+        out_ref = np.concatenate(parts)
     out_gpu = out[torch.from_numpy(tokens.astype(np.int64)).cuda()].float().cpu().numpy()
     report["output"] = assert_output(out_gpu, out_ref, "layer output (%s)" % cfg.name)
     if out16 is not None:
