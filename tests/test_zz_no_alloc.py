@@ -48,3 +48,39 @@ def test_static_scratch_layer_equals_layer_twice_in_a_row_second_smaller():
         assert (out == 0).all()
     finally:
         moe.close()
+
+
+def test_static_scratch_layer_in_a_hip_graph():
+    """The callers the entry point is for: captured once (after one eager call, which uploads the
+    weight pointer table), replayed with eager work and synchronisations in between; every replay
+    gives moe_layer's bits."""
+    from paper_2503_09716_amd import Moe
+    moe = Moe(0)
+    try:
+        cfg = scaled_config("C4", T=333, H=256, F=192)
+        gl = P.GpuLayer(moe, make_layer_inputs(cfg, device="cuda"), host_weights=False)
+        ref = gl.run_layer().clone()
+        out = torch.empty_like(ref)
+
+        def step():
+            moe.layer_static(gl.shape, gl.x, gl.wg, gl.bias, gl.w1p, gl.w3p, gl.w2p, out, tables=gl.tables)
+
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        torch.cuda.synchronize()
+        for _ in range(3):
+            out.zero_()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out, ref)
+            assert torch.equal(gl.run_layer(), ref)      # eager work of the library between replays
+    finally:
+        moe.close()
