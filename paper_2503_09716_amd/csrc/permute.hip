@@ -4,13 +4,16 @@
 //
 // Canonical order = ascending expert id, then ascending token id, so the result is unique
 // and every run is bit-identical.  Tokens are cut into chunks of PERMUTE_CHUNK_TOKENS; one
-// wavefront owns one chunk:
+// workgroup owns one chunk:
 //   count : per-chunk per-expert histogram
 //   scan  : per-expert exclusive prefix over chunks, then exclusive prefix over experts
-//   place : the wavefront walks its chunk 64 tokens at a time; a 64-bit lane mask per expert
-//           (built with integer OR in LDS) gives each token its rank (popcount of lower
-//           lanes); the running per-expert cursors stay in LDS
+//   place : a 64-bit lane mask per expert and wavefront (built with integer OR in LDS) gives
+//           each (token, rank) pair its position among its expert's rows of the chunk
+//           (popcount of the lower lanes and of the lower wavefronts' masks)
 //   gather: x_perm[r,:] = x[perm[r]/k,:] in 16-byte pieces, one row per wavefront pass
+// Launches: one for small batches (every workgroup counts everything itself), two for the
+// usual sizes (count; scan + place), three when the table of histograms is too large for every
+// workgroup to add up.
 #include "common.h"
 
 namespace moe {
@@ -18,22 +21,22 @@ namespace {
 
 constexpr int MAX_E = 256;
 
-__global__ __launch_bounds__(64) void permute_count_kernel(const int32_t* __restrict__ idx, int T, int k, int E,
-                                                           int32_t* __restrict__ chunk_counts) {
+__global__ __launch_bounds__(256) void permute_count_kernel(const int32_t* __restrict__ idx, int T, int k, int E,
+                                                            int32_t* __restrict__ chunk_counts) {
     __shared__ int cnt[MAX_E];
-    const int lane = threadIdx.x, chunk = blockIdx.x;
-    for (int e = lane; e < E; e += 64) cnt[e] = 0;
+    const int tid = threadIdx.x, chunk = blockIdx.x;
+    for (int e = tid; e < E; e += 256) cnt[e] = 0;
     __syncthreads();
     const int t0 = chunk * PERMUTE_CHUNK_TOKENS;
     const int t1 = min(T, t0 + PERMUTE_CHUNK_TOKENS);
     const int n = (t1 - t0) * k;
     const int32_t* p = idx + (size_t)t0 * k;
-    for (int i = lane; i < n; i += 64) {
+    for (int i = tid; i < n; i += 256) {
         const int e = p[i];
         if ((unsigned)e < (unsigned)E) atomicAdd(&cnt[e], 1);  // integer LDS counters: order-independent
     }
     __syncthreads();
-    for (int e = lane; e < E; e += 64) chunk_counts[(size_t)chunk * E + e] = cnt[e];
+    for (int e = tid; e < E; e += 256) chunk_counts[(size_t)chunk * E + e] = cnt[e];
 }
 
 // chunk_counts[c][e] -> exclusive prefix over c (in place); offsets[e] = exclusive prefix over experts.
@@ -116,44 +119,18 @@ __global__ __launch_bounds__(64) void permute_place_kernel(const int32_t* __rest
     }
 }
 
-// All three steps in ONE launch, for small batches (T*k <= FUSED_MAX_PAIRS), where two extra
-// launches cost more than the work (256 tokens top-2: 6 us against 13; from a few thousand pairs
-// on, the three kernels win: every workgroup here reads the whole index array): every workgroup
-// (one per chunk, 4 wavefronts) histograms ALL pairs into wave-private LDS counters, once counting everything (-> expert_offsets, the same in
-// every workgroup) and once counting only the chunks before its own (-> its cursors), then
-// places its chunk: wavefront w takes tokens 64w .. 64w+63 of the chunk, the lane masks of all
-// four wavefronts give a pair its rank.  Same result as the three kernels above, bit for bit,
-// without their two extra launches.
-constexpr int FUSED_MAX_PAIRS = 1 << 12;
-static_assert(PERMUTE_CHUNK_TOKENS == 256, "the fused kernel gives each of its 4 wavefronts 64 tokens of a chunk");
-
-__global__ __launch_bounds__(256) void permute_index_fused_kernel(const int32_t* __restrict__ idx, int T, int k, int E,
-                                                                  int32_t* __restrict__ offsets, int32_t* __restrict__ perm,
-                                                                  int32_t* __restrict__ inv_perm, int32_t* __restrict__ row_token) {
-    __shared__ int hist[4][2][MAX_E];              // [wave][0: all chunks, 1: chunks before mine][expert]
-    __shared__ unsigned long long mask[4][MAX_E];  // [wave][expert]: lanes of that wave that picked the expert
-    __shared__ int cur[MAX_E];
-    __shared__ int wave_sum[4];
+// Common tail of the two kernels below.  Thread e < E comes in with its expert's pair count over
+// all chunks (total) and over the chunks before this workgroup's (before); mask[][] is zero.
+// Exclusive prefix sum of the totals over the experts (-> expert_offsets, written by chunk 0, and
+// this chunk's cursors), then the placement of the chunk: wavefront w takes tokens 64w .. 64w+63,
+// the lane masks of all four wavefronts give a pair its rank.
+__device__ __forceinline__ void scan_and_place_chunk(const int32_t* __restrict__ idx, const int T, const int k, const int E,
+                                                     const int total, const int before,
+                                                     unsigned long long (&mask)[4][MAX_E], int (&cur)[MAX_E],
+                                                     int (&wave_sum)[4], int32_t* __restrict__ offsets,
+                                                     int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm,
+                                                     int32_t* __restrict__ row_token) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, chunk = blockIdx.x;
-    for (int i = tid; i < 4 * 2 * MAX_E; i += 256) (&hist[0][0][0])[i] = 0;
-    for (int i = tid; i < 4 * MAX_E; i += 256) (&mask[0][0])[i] = 0ull;
-    __syncthreads();
-    const int n = T * k;
-    const int mine_begin = chunk * PERMUTE_CHUNK_TOKENS * k;   // pairs of earlier chunks come before this index
-    for (int i = tid; i < n; i += 256) {
-        const int e = idx[i];
-        if ((unsigned)e < (unsigned)E) {
-            atomicAdd(&hist[wave][0][e], 1);                   // integer LDS counters: order-independent
-            if (i < mine_begin) atomicAdd(&hist[wave][1][e], 1);
-        }
-    }
-    __syncthreads();
-    // thread e: totals of expert e, then an exclusive prefix sum over the experts (E <= 256 = one per thread)
-    int total = 0, before = 0;
-    if (tid < E) {
-#pragma unroll
-        for (int w = 0; w < 4; ++w) { total += hist[w][0][tid]; before += hist[w][1][tid]; }
-    }
     int incl = total;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
@@ -193,6 +170,82 @@ __global__ __launch_bounds__(256) void permute_index_fused_kernel(const int32_t*
             inv_perm[(size_t)t * k + j] = slot;
             if (row_token) row_token[slot] = t;
         }
+}
+
+// All three steps in ONE launch, for small batches (T*k <= FUSED_MAX_PAIRS), where two extra
+// launches cost more than the work (256 tokens top-2: 6 us against 13; from a few thousand pairs
+// on, the three kernels win: every workgroup here reads the whole index array): every workgroup
+// (one per chunk, 4 wavefronts) histograms ALL pairs into wave-private LDS counters, once counting everything (-> expert_offsets, the same in
+// every workgroup) and once counting only the chunks before its own (-> its cursors), then
+// places its chunk: wavefront w takes tokens 64w .. 64w+63 of the chunk, the lane masks of all
+// four wavefronts give a pair its rank.  Same result as the three kernels above, bit for bit,
+// without their two extra launches.
+constexpr int FUSED_MAX_PAIRS = 1 << 12;
+static_assert(PERMUTE_CHUNK_TOKENS == 256, "the fused kernel gives each of its 4 wavefronts 64 tokens of a chunk");
+
+__global__ __launch_bounds__(256) void permute_index_fused_kernel(const int32_t* __restrict__ idx, int T, int k, int E,
+                                                                  int32_t* __restrict__ offsets, int32_t* __restrict__ perm,
+                                                                  int32_t* __restrict__ inv_perm, int32_t* __restrict__ row_token) {
+    __shared__ int hist[4][2][MAX_E];              // [wave][0: all chunks, 1: chunks before mine][expert]
+    __shared__ unsigned long long mask[4][MAX_E];  // [wave][expert]: lanes of that wave that picked the expert
+    __shared__ int cur[MAX_E];
+    __shared__ int wave_sum[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, chunk = blockIdx.x;
+    for (int i = tid; i < 4 * 2 * MAX_E; i += 256) (&hist[0][0][0])[i] = 0;
+    for (int i = tid; i < 4 * MAX_E; i += 256) (&mask[0][0])[i] = 0ull;
+    __syncthreads();
+    const int n = T * k;
+    const int mine_begin = chunk * PERMUTE_CHUNK_TOKENS * k;   // pairs of earlier chunks come before this index
+    for (int i = tid; i < n; i += 256) {
+        const int e = idx[i];
+        if ((unsigned)e < (unsigned)E) {
+            atomicAdd(&hist[wave][0][e], 1);                   // integer LDS counters: order-independent
+            if (i < mine_begin) atomicAdd(&hist[wave][1][e], 1);
+        }
+    }
+    __syncthreads();
+    int total = 0, before = 0;
+    if (tid < E) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) { total += hist[w][0][tid]; before += hist[w][1][tid]; }
+    }
+    scan_and_place_chunk(idx, T, k, E, total, before, mask, cur, wave_sum, offsets, perm, inv_perm, row_token);
+}
+
+// Scan + placement in one launch, from the per-chunk histograms of permute_count_kernel: every
+// workgroup adds up the histograms of all chunks (-> expert_offsets) and of the chunks before its
+// own (-> its cursors), then places its chunk like the kernel above.  Thread i sums expert
+// i % EP2 over the chunks i / EP2, i / EP2 + 256 / EP2, ... (EP2 = E rounded up to a power of two),
+// the partial sums meet in integer LDS counters.  nchunks * E integers are read by every
+// workgroup, so the launcher takes this path only while that stays small.
+constexpr int PLACE_SCAN_MAX_COUNTS = 1 << 14;
+
+__global__ __launch_bounds__(256) void permute_place_scan_kernel(const int32_t* __restrict__ idx, int T, int k, int E, int ep2,
+                                                                 const int32_t* __restrict__ chunk_counts, int nchunks,
+                                                                 int32_t* __restrict__ offsets, int32_t* __restrict__ perm,
+                                                                 int32_t* __restrict__ inv_perm, int32_t* __restrict__ row_token) {
+    __shared__ int sum[2][MAX_E];                  // [0: all chunks, 1: chunks before mine][expert]
+    __shared__ unsigned long long mask[4][MAX_E];
+    __shared__ int cur[MAX_E];
+    __shared__ int wave_sum[4];
+    const int tid = threadIdx.x, chunk = blockIdx.x;
+    for (int i = tid; i < 2 * MAX_E; i += 256) (&sum[0][0])[i] = 0;
+    for (int i = tid; i < 4 * MAX_E; i += 256) (&mask[0][0])[i] = 0ull;
+    __syncthreads();
+    const int e = tid & (ep2 - 1), step = 256 / ep2;
+    if (e < E) {
+        int all = 0, before = 0;
+        for (int c = tid / ep2; c < nchunks; c += step) {
+            const int v = chunk_counts[(size_t)c * E + e];
+            all += v;
+            if (c < chunk) before += v;
+        }
+        atomicAdd(&sum[0][e], all);                // integer LDS counters: order-independent
+        atomicAdd(&sum[1][e], before);
+    }
+    __syncthreads();
+    const int total = tid < E ? sum[0][tid] : 0, before = tid < E ? sum[1][tid] : 0;
+    scan_and_place_chunk(idx, T, k, E, total, before, mask, cur, wave_sum, offsets, perm, inv_perm, row_token);
 }
 
 // One wavefront copies one row per pass; 16 bytes per lane, consecutive lanes consecutive addresses.
@@ -250,7 +303,14 @@ hipError_t launch_permute_index(const moe_shape& s, const int32_t* idx, int32_t*
                            inv_perm, row_token);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL(permute_count_kernel, dim3(nchunks), dim3(64), 0, st, idx, s.T, s.top_k, s.E, chunk_counts);
+    hipLaunchKernelGGL(permute_count_kernel, dim3(nchunks), dim3(256), 0, st, idx, s.T, s.top_k, s.E, chunk_counts);
+    if ((int64_t)nchunks * s.E <= PLACE_SCAN_MAX_COUNTS) {
+        int ep2 = 1;
+        while (ep2 < s.E) ep2 <<= 1;
+        hipLaunchKernelGGL(permute_place_scan_kernel, dim3(nchunks), dim3(256), 0, st, idx, s.T, s.top_k, s.E, ep2,
+                           (const int32_t*)chunk_counts, nchunks, offsets, perm, inv_perm, row_token);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(256), 0, st, chunk_counts, nchunks, s.E, offsets);
     hipLaunchKernelGGL(permute_place_kernel, dim3(nchunks), dim3(64), 0, st, idx, s.T, s.top_k, s.E,
                        (const int32_t*)chunk_counts, (const int32_t*)offsets, perm, inv_perm, row_token);

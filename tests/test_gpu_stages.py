@@ -121,7 +121,9 @@ def random_routing(rng, T, E, k, skew=None):
 # One launch up to 4096 pairs, beyond that histogram / scan / placement are three launches
 PERMUTE_CASES = [(256, 8, 2, None), (1000, 64, 6, None), (777, 160, 6, "one"), (1, 4, 1, None), (300, 5, 5, None),
                  (2049, 37, 3, None), (682, 256, 6, None), (683, 256, 6, None), (500, 160, 6, "one"), (12000, 37, 6, "one"),
-                 (32768, 8, 2, None), (16384, 16, 4, None), (16385, 16, 4, None), (4099, 13, 3, "one"), (1025, 17, 4, None)]
+                 (32768, 8, 2, None), (16384, 16, 4, None), (16385, 16, 4, None), (4099, 13, 3, "one"), (1025, 17, 4, None),
+                 (40000, 256, 2, None), (16384, 160, 8, None), (16640, 64, 6, "one"), (16385, 64, 1, None),
+                 (16384, 256, 1, None), (16385, 256, 1, None)]
 
 
 @pytest.mark.parametrize("T,E,k,skew", PERMUTE_CASES)
