@@ -33,7 +33,7 @@
  *    logical [H,F] / [F,H] matrices (same number of bytes): the transposed matrix W[n][k]
  *    (k = contraction index) is cut into blocks of 16 rows x 32 k = 1 KiB, blocks ordered
  *    [N/16][K/32]; inside a block, row r (0..15) occupies bytes 64r..64r+63 and its 16-byte
- *    piece c (k = 8c..8c+7) sits at slot c ^ ((r/4)&3); rows keep their logical order.
+ *    piece c (k = 8c..8c+7) sits at slot c ^ ((4 - r/4) & 3); rows keep their logical order.
  *    Weights are static, so packing is not part of the timed path.
  *  - Limits: H % 64 == 0, F % 64 == 0, 1 <= top_k <= E <= 256, top_k <= 64,
  *    0 <= num_shared <= 8, every matrix below 4 GiB.  Other shapes: MOE_E_UNSUPPORTED.

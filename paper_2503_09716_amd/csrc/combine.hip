@@ -65,7 +65,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const char* __restrict__ y
 // One-time weight packing.  in: logical [K, N] bf16 row-major (K = contraction dimension).
 // out: the tiled layout the GEMM loads, i.e. the matrix W[n][k] = in[k][n] cut into blocks of
 // 16 rows x 32 k (1 KiB), blocks ordered [N/16][K/32]; inside a block, row r (0..15) occupies
-// bytes r*64..r*64+63 and its 16-byte piece c (k = 8c..8c+7) sits at slot c ^ ((r/4)&3).
+// bytes r*64..r*64+63 and its 16-byte piece c (k = 8c..8c+7) sits at slot c ^ ((4 - r/4) & 3).
 // Rows keep their logical order.
 // One workgroup transposes a 32 k x 32 n patch through LDS.
 // N columns exist in `in`; blocks past them (the router pads its expert count to 32) are zero.
@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const uint16_t* __rest
         // 2 groups x 64 pieces; piece id inside the group = r*4 + slot
         const int grp = tid >> 6, pid = tid & 63;
         const int r = pid >> 2, slot = pid & 3;
-        const int c = slot ^ ((r >> 2) & 3);
+        const int c = slot ^ block_swizzle(r);
         const int rho = grp * 16 + r;
         const int nloc = rho;
         uint16_t v[8];

@@ -105,6 +105,17 @@ hipError_t launch_route(const moe_shape& s, const void* x, const void* wg, const
 hipError_t launch_route_topk(const moe_shape& s, const float* partial, int splits, int ep, const float* bias,
                              int32_t* idx, float* w, float* logits, hipStream_t st);
 
+// Swizzle of the 1 KiB operand blocks (16 rows x 64 bytes, in LDS and in every tiled global
+// layout): the logical 16-byte piece c of row r (0..15) sits at slot c ^ block_swizzle(r).
+// ds_read_b128 serves a wave's 64 lanes in four passes of 16, and not 16 consecutive ones:
+// lanes {0-3, 12-15, 20-27}, {4-11, 16-19, 28-31} and the same two sets + 32 (measured lane
+// pair by lane pair with the LDS bank-conflict counter).  An MFMA operand read has lane l on
+// row l % 16, piece l / 16, so a pass covers row quads {0, 3} of one piece and {1, 2} of the
+// next: with (4 - r/4) % 4 the four quads of a pass land in four different slots and its 16
+// lanes in 16 different 16-byte bank groups (r/4 itself puts quads 0 and 1, 2 and 3 of a pass
+// in the same slot: every read took twice the cycles).
+__host__ __device__ constexpr int block_swizzle(const int r) { return (0 - (r >> 2)) & 3; }
+
 constexpr int PERMUTE_CHUNK_TOKENS = 256;
 inline int permute_chunks(const moe_shape& s) { return (s.T + PERMUTE_CHUNK_TOKENS - 1) / PERMUTE_CHUNK_TOKENS; }
 hipError_t launch_permute_index(const moe_shape& s, const int32_t* idx, int32_t* chunk_counts, int32_t* offsets,

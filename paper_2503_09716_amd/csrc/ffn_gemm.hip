@@ -26,8 +26,8 @@
 //     are spread between the MFMAs (one every few) instead of bursting after the barrier.
 //     One barrier per sub-tile; s_waitcnt vmcnt(n) waits only for the sub-tile needed next.
 //   * LDS layout: 64-byte rows (32 bf16), the four 16-byte pieces of a row XOR-swizzled by
-//     (row / 4) & 3 so the 16-byte MFMA operand reads of 16 consecutive rows fall in distinct
-//     banks.  The swizzle is applied by choosing which global piece each lane of the
+//     (4 - row / 4) & 3 so that each of the four 16-lane passes in which the LDS serves a
+//     16-byte MFMA operand read falls in distinct banks (block_swizzle).  The swizzle is applied by choosing which global piece each lane of the
 //     direct-to-LDS load fetches, since the LDS side of that load is fixed (lane * 16 bytes).
 //   * v_mfma_f32_16x16x32_bf16: one instruction multiplies a 16-row block of each operand over
 //     the whole sub-tile.  In a register-only loop on this workload's data it sustains 1.98
@@ -196,14 +196,14 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
 
     // ------------------------------------------------------------------ loader setup
     // Wave-load q fills LDS bytes [q*1024, q*1024+1024) of a stage: 16 rows x 4 pieces.
-    // Lane l supplies row q*16 + l/4, slot l%4, which must hold logical piece (l%4) ^ ((l/16)&3).
+    // Lane l supplies row q*16 + l/4, slot l%4, which must hold logical piece (l%4) ^ block_swizzle(l/4).
     // This wave owns q = i*NW + wave; the X region is padded to a multiple of NW wave-loads so
     // that load i is an X load for i < NLX and a W load otherwise, for every wave.
     // Loads are buffer loads: address = operand base (SGPR descriptor) + per-lane offset (VGPR,
     // fixed for the whole tile) + K offset (SGPR, advanced per sub-tile), so the K loop needs no
     // vector address arithmetic at all.
     const int lrow = lane >> 2;
-    const int lpiece = (lane & 3) ^ ((lane >> 4) & 3);
+    const int lpiece = (lane & 3) ^ block_swizzle(lrow);
     uint32_t loff[NL];
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
@@ -217,9 +217,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
                 if (!shared && p.row_token) grow = p.row_token[grow];
                 loff[i] = (uint32_t)grow * (uint32_t)p.lda_bytes + (uint32_t)(lpiece * 16);
             } else {
-                // h: tiled; the piece this lane needs sits at slot piece ^ ((row%16)/4) of its row
+                // h: tiled; the piece this lane needs sits at slot piece ^ block_swizzle(row%16) of its row
                 const int rr = grow & 15;
-                loff[i] = (uint32_t)(grow >> 4) * (uint32_t)(p.kt_a * 1024) + (uint32_t)(rr * 64 + ((lpiece ^ (rr >> 2)) << 4));
+                loff[i] = (uint32_t)(grow >> 4) * (uint32_t)(p.kt_a * 1024) + (uint32_t)(rr * 64 + ((lpiece ^ block_swizzle(rr)) << 4));
             }
         } else {
             // W: tiled by the pack step, so LDS rows (q-NQX)*16 .. +15 of the W region
@@ -244,12 +244,12 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
 
     // ------------------------------------------------------------------ reader setup
     // Lane l reads row (l & 15) of a 16-row block, logical piece l >> 4 (k = 8*(l>>4) .. +7),
-    // stored at slot piece ^ ((row / 4) & 3).  Block bases are multiples of 16 rows, so the
+    // stored at slot piece ^ block_swizzle(row).  Block bases are multiples of 16 rows, so the
     // swizzle term depends on the lane only.
     const int rl = lane & 15, g = lane >> 4;
     const int bx0 = wm * TI;                       // in 32-row units
     const int bw0 = GATED ? wn * TJH : wn * TJ;    // in 32-row units
-    const uint32_t offL = (uint32_t)(rl * ROWB + ((g ^ ((rl >> 2) & 3)) << 4));
+    const uint32_t offL = (uint32_t)(rl * ROWB + ((g ^ block_swizzle(rl)) << 4));
     const uint32_t offX = offL + (uint32_t)(bx0 * 32 * ROWB);
     const uint32_t offW = offL + (uint32_t)(XBYTES + bw0 * 32 * ROWB);
 
@@ -400,13 +400,13 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& p, const TileDesc d, c
         // W is the row operand: the lane owns output row (X row) lane%16 of block i and the 4
         // consecutive columns 4*(lane/16) .. +3 of gate block j; the up value of the same
         // element sits in the same lane and register of block WBH + j.  h is written tiled:
-        // block (row/16, col/32), row%16 at 64 bytes each, piece slot = piece ^ ((row%16)/4);
+        // block (row/16, col/32), row%16 at 64 bytes each, piece slot = piece ^ block_swizzle(row%16);
         // a store instruction covers 16 rows x 32 contiguous bytes.
 #pragma unroll
         for (int i = 0; i < XB; ++i) {
             const int r = bx0 * 32 + i * 16 + rl;
             const bool row_ok = r < d.nrows;
-            const int ro = orow_base + r, rr = ro & 15, sw = rr >> 2;
+            const int ro = orow_base + r, rr = ro & 15, sw = block_swizzle(rr);
             char* hrow = out + ((size_t)(ro >> 4) * (size_t)(N >> 5)) * 1024 + rr * 64;
 #pragma unroll
             for (int j = 0; j < WBH; ++j) {

@@ -263,7 +263,7 @@ __global__ __launch_bounds__(256) void permute_gather_kernel(const uint4* __rest
 }
 
 // Gather into the tiled layout: one wavefront fills one 1 KiB block (16 permuted rows x 32
-// columns): lane l reads the 16-byte piece ((l%4) ^ ((l/16)%4)) of row 16g + l/4 and writes
+// columns): lane l reads the 16-byte piece (l%4) ^ block_swizzle(l/4) of row 16g + l/4 and writes
 // slot l of the block, so every store instruction covers 1 KiB of consecutive memory.
 __global__ __launch_bounds__(256) void permute_gather_tiled_kernel(const char* __restrict__ x,
                                                                    const int32_t* __restrict__ row_token, int R, int H,
@@ -272,7 +272,7 @@ __global__ __launch_bounds__(256) void permute_gather_tiled_kernel(const char* _
     const int KT = H >> 5;
     const int nblocks = ((R + 15) >> 4) * KT;
     const int nwaves = gridDim.x * 4;
-    const int piece = (lane & 3) ^ ((lane >> 4) & 3);
+    const int piece = (lane & 3) ^ block_swizzle(lane >> 2);
     for (int b = blockIdx.x * 4 + (threadIdx.x >> 6); b < nblocks; b += nwaves) {
         const int g = b / KT, kt = b - g * KT;
         int r = g * 16 + (lane >> 2);

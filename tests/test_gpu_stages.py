@@ -370,7 +370,7 @@ def packed_reference(w: np.ndarray) -> np.ndarray:
         for kt in range(K // 32):
             base = (g * (K // 32) + kt) * 512
             for c in range(4):
-                slot = c ^ ((r // 4) & 3)
+                slot = c ^ ((4 - r // 4) & 3)
                 out[base + r * 32 + slot * 8: base + r * 32 + slot * 8 + 8] = w[kt * 32 + c * 8: kt * 32 + c * 8 + 8, src]
     return out
 
