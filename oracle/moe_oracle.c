@@ -17,7 +17,8 @@
  *
  * Parity pins: see tests/test_oracle_pins.py (brute force, closed forms, dense SwiGLU per
  * expert against an independent library routine, two hand-computed examples, fp32 and bf16
- * inputs of the combine against a float64 sum).
+ * inputs of the combine against a float64 sum).  tests/test_oracle_mutations.py plants single
+ * mistakes into scratch copies of this file and requires those pins to fail on each.
  */
 #include <math.h>
 #include <stdint.h>
