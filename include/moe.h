@@ -136,9 +136,9 @@ size_t moe_h_scratch_bytes(const moe_shape* shape);
  *                             Its y_shared is always fp32.
  *   "out_fp32"        0 | 1   dtype of the layer output written by moe_combine / moe_layer:
  *                             0 (default) bf16 = round-to-nearest-even of the fp32 sum, 1 fp32
- *   "gate_packed"     0 | 1   1: for shapes with E > 16 the wg_bf16 argument of moe_route and of every moe_layer
- *                             variant is the packed gate matrix made by moe_pack_gate (the router then skips
- *                             its per-call packing launch); shapes with E <= 16 are not affected.  Default 0. */
+ *   "gate_packed"     0 | 1   1: the wg_bf16 argument of moe_route and of every moe_layer variant is the packed
+ *                             gate matrix made by moe_pack_gate (the router then skips its per-call packing
+ *                             launch).  Default 0. */
 moe_status moe_set_option(moe_ctx* ctx, const char* key, int32_t value);
 
 /* One-time weight packing: w_logical [rows, cols] bf16 (device; rows = contraction dimension)
@@ -147,12 +147,12 @@ moe_status moe_set_option(moe_ctx* ctx, const char* key, int32_t value);
 moe_status moe_pack_weight(moe_ctx* ctx, const void* w_logical, int32_t rows, int32_t cols,
                            void* w_packed, void* hip_stream);
 
-/* One-time packing of the gate matrix for shapes whose router runs on the matrix cores (E > 16):
+/* One-time packing of the gate matrix (the router multiplies x with it on the matrix cores):
  * wg_bf16 [H,E] logical (device) -> wg_packed (device, moe_gate_packed_bytes(shape) bytes: the
  * expert count padded to a multiple of 32 with zero rows, in the packed weight layout).  The gate
  * matrix is static like the expert weights, so this cost is outside the timed path; pass the
- * result as wg_bf16 under option "gate_packed" = 1.  moe_gate_packed_bytes is 0 and moe_pack_gate
- * returns MOE_E_ARG when E <= 16 (the streaming router reads the logical layout). */
+ * result as wg_bf16 under option "gate_packed" = 1.  Without it every call packs the matrix into
+ * its workspace first (one small launch). */
 size_t moe_gate_packed_bytes(const moe_shape* shape);
 moe_status moe_pack_gate(moe_ctx* ctx, const moe_shape* shape, const void* wg_bf16, void* wg_packed, void* hip_stream);
 
@@ -165,8 +165,8 @@ moe_status moe_pack_gate(moe_ctx* ctx, const moe_shape* shape, const void* wg_bf
  *   gate_bias [E] fp32 device or NULL
  *   topk_idx [T,k] int32 device out, topk_w [T,k] fp32 device out,
  *   logits_or_null [T,E] fp32 device out (for near-tie reports) or NULL
- *   workspace: device, at least moe_workspace_bytes(shape) (used when E > 16: the gate GEMM then
- *   runs on the matrix cores and keeps its packed gate matrix and partial logits there). */
+ *   workspace: device, at least moe_workspace_bytes(shape) (holds the packed gate matrix unless the
+ *   caller passes it packed and, for E > 16, the partial logits of the gate GEMM). */
 moe_status moe_route(moe_ctx* ctx, const moe_shape* shape, const void* x_bf16, const void* wg_bf16,
                      const float* gate_bias, int32_t* topk_idx, float* topk_w, float* logits_or_null,
                      void* workspace, size_t workspace_bytes, void* hip_stream);

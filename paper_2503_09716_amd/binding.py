@@ -187,7 +187,7 @@ class Moe:
         return out
 
     def pack_gate(self, shape, wg: torch.Tensor):
-        """Packed gate matrix for option "gate_packed" (None when the shape's router does not use one)."""
+        """Packed gate matrix for option "gate_packed"."""
         n = int(self.lib.moe_gate_packed_bytes(C.byref(shape)))
         if n == 0:
             return None

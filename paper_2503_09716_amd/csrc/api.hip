@@ -105,14 +105,15 @@ inline size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
 // Router through the GEMM tile routine (E > 16): experts padded to 32, K cut into `splits`
 // independent accumulation chains (shorter fp32 sums, and more tiles to fill the CUs), tiles
-// of `tm` tokens.  splits == 0: the streaming kernel is used instead.
+// of `tm` tokens.  splits == 0 (E <= 16): one kernel does the contraction and the selection; `ep`
+// (rows of the packed gate matrix) is valid for every shape.
 struct RouteGemm {
     int splits, ep, tm;
 };
 RouteGemm route_gemm_config(const moe_shape& s) {
     RouteGemm r{0, 0, 0};
-    if (s.E <= 16) return r;
-    r.ep = (s.E + 31) & ~31;
+    r.ep = (s.E + 31) & ~31;   // rows of the packed gate matrix (zero rows past E)
+    if (s.E <= 16) return r;   // splits = 0: no gate GEMM launch, route_mfma_kernel does it all
     r.splits = (s.H % 256 == 0 && s.H >= 1024) ? 4 : (s.H % 128 == 0 ? 2 : 1);
     r.tm = (int64_t)r.splits * ((s.T + 255) / 256) >= 512 ? 256 : 128;
     return r;
@@ -153,9 +154,9 @@ Layout make_layout(const moe_shape& s) {
     L.descs_down = take(((size_t)max_mtiles(s, 128) + (size_t)s.E * (dsp - 1)) * sizeof(TileDesc));
     L.split_tails = take((size_t)s.E * sizeof(SplitTail));
     L.split_partial = take(dsp > 1 ? (size_t)s.E * dsp * SPLIT_TAIL_ROWS * s.H * 4 : 0);
-    // router GEMM (E > 16): packed gate matrix (unless the caller passes it packed), partial logits
+    // router: packed gate matrix (unless the caller passes it packed); E > 16: partial logits of the gate GEMM
     const RouteGemm rg = route_gemm_config(s);
-    L.rt_wg = take(rg.splits ? (size_t)rg.ep * s.H * 2 : 0);
+    L.rt_wg = take((size_t)rg.ep * s.H * 2);
     L.rt_logits = take(rg.splits ? (size_t)rg.splits * s.T * rg.ep * 4 : 0);
     L.x_tiled = take(((R + 15) & ~(size_t)15) * s.H * 2);
     L.h = take((size_t)h_rows(s) * s.F * 2);
@@ -245,12 +246,7 @@ moe_status weight_table(moe_ctx* c, int n, const void* const* w1, const void* co
 moe_status run_route(moe_ctx* c, const moe_shape& s, const void* x, const void* wg, const float* bias, int32_t* idx,
                      float* w, float* logits, char* ws, hipStream_t st) {
     const RouteGemm rg = route_gemm_config(s);
-    if (!rg.splits) {
-        HIP_TRY(c, launch_route(s, x, wg, bias, idx, w, logits, st));
-        return MOE_OK;
-    }
     const Layout L = make_layout(s);
-    const int k_split = s.H / rg.splits;
     // The gate matrix is static: a caller that packs it once (moe_pack_gate, option "gate_packed")
     // spares every call this launch.
     const char* wg_packed = (const char*)wg;
@@ -258,6 +254,12 @@ moe_status run_route(moe_ctx* c, const moe_shape& s, const void* x, const void* 
         HIP_TRY(c, launch_pack_weight(wg, s.H, s.E, rg.ep, ws + L.rt_wg, st));
         wg_packed = ws + L.rt_wg;
     }
+    if (!rg.splits) {
+        // E <= 16: one kernel, logits on the matrix cores and the selection in the same workgroup
+        HIP_TRY(c, launch_route_mfma(s, x, wg_packed, bias, idx, w, logits, st));
+        return MOE_OK;
+    }
+    const int k_split = s.H / rg.splits;
     GemmArgs a;
     memset(&a, 0, sizeof(a));
     a.a_routed = (const char*)x;
@@ -611,14 +613,12 @@ moe_status moe_pack_weight(moe_ctx* c, const void* w, int32_t rows, int32_t cols
 size_t moe_gate_packed_bytes(const moe_shape* s) {
     moe_status st;
     if (shape_problem(s, &st)) return 0;
-    const RouteGemm rg = route_gemm_config(*s);
-    return rg.splits ? (size_t)rg.ep * s->H * 2 : 0;
+    return (size_t)route_gemm_config(*s).ep * s->H * 2;
 }
 
 moe_status moe_pack_gate(moe_ctx* c, const moe_shape* s, const void* wg, void* wg_packed, void* stream) {
     if (moe_status st = check_common(c, s)) return st;
     const RouteGemm rg = route_gemm_config(*s);
-    if (!rg.splits) return fail(c, MOE_E_ARG, "pack_gate: with E <= 16 the router reads the gate matrix as it is");
     if (!wg || !wg_packed || wg == wg_packed) return fail(c, MOE_E_ARG, "pack_gate: NULL or aliased buffers");
     HIP_TRY(c, launch_pack_weight(wg, s->H, s->E, rg.ep, wg_packed, (hipStream_t)stream));
     return MOE_OK;

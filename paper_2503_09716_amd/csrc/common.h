@@ -99,8 +99,8 @@ inline int64_t max_mtiles(const moe_shape& s, int tm) {
 }
 
 // ---- launchers (each only enqueues on `st`; returns the launch status) ----
-hipError_t launch_route(const moe_shape& s, const void* x, const void* wg, const float* bias, int32_t* idx,
-                        float* w, float* logits, hipStream_t st);   // E <= 16: one streaming kernel
+hipError_t launch_route_mfma(const moe_shape& s, const void* x, const void* wg_packed, const float* bias, int32_t* idx,
+                             float* w, float* logits, hipStream_t st);   // E <= 16: one kernel, x against the packed gate matrix
 // softmax + top-k from `splits` fp32 partial logit matrices [splits][T][ep]
 hipError_t launch_route_topk(const moe_shape& s, const float* partial, int splits, int ep, const float* bias,
                              int32_t* idx, float* w, float* logits, hipStream_t st);

@@ -3,13 +3,15 @@
 //
 // bf16 x bf16 products are exact in fp32, so the GPU logits differ from a correctly rounded
 // reference only through the order of the fp32 additions; both paths below keep the sums short
-// enough that top-k agrees except at genuine near-ties.
-//   E <= 16 : one streaming kernel (HBM-bound): fp32 FMAs per lane, reduction over lanes and waves.
-//   E  > 16 : the logits are a dense contraction and go through the MFMA tile routine of the
-//             grouped GEMM (x against the packed gate matrix, K cut into independent chains);
-//             route_topk_kernel then sums the partials, adds the bias and selects.
-// Selection: 64 lanes hold a token's logits, max / sum are butterfly reductions and top-k is k
-// rounds of a wave-wide arg-max on the logits (ties resolved towards the lower expert id).
+// enough that top-k agrees except at genuine near-ties.  Both multiply x with the PACKED gate
+// matrix on the matrix cores:
+//   E <= 16 : one kernel (HBM-bound: it streams x once): 16 tokens per workgroup, K cut over 8
+//             waves, the selection in the same workgroup with a token's logits in 16 lanes.
+//   E  > 16 : the logits go through the MFMA tile routine of the grouped GEMM (K cut into
+//             independent chains); route_topk_kernel then sums the partials, adds the bias and
+//             selects: 64 lanes hold a token's logits.
+// Selection: max / sum are butterfly reductions and top-k is k rounds of an arg-max on the
+// logits (ties resolved towards the lower expert id).
 #include <type_traits>
 
 #include "common.h"
@@ -127,100 +129,108 @@ __device__ __forceinline__ void route_finish(const float (&v)[NV], const int lan
     }
 }
 
-// Sum over the 64 lanes of N per-lane values (N = 64 or 128) in N - N/64 exchange steps instead
-// of 6N: at the step with lane mask m every lane keeps one half of its values (upper half if its
-// bit m is set) and adds the partner's copy of that half.  Afterwards lane l holds the complete
-// sums of values l*(N/64) .. +N/64-1 in v[0..N/64).  fp32 addition is commutative, so every value
-// is added up along the same tree of lanes whatever its index.
-template <int N, int HALF = N / 2, int MASK = 32>
-__device__ __forceinline__ void lane_reduce_scatter(float (&v)[N], const int lane) {
-    const bool up = (lane & MASK) != 0;
-#pragma unroll
-    for (int i = 0; i < HALF; ++i) {
-        const float keep = up ? v[i + HALF] : v[i];
-        const float send = up ? v[i] : v[i + HALF];
-        v[i] = keep + pair_f<MASK>(send);
-    }
-    if constexpr (MASK > 1) lane_reduce_scatter<N, HALF / 2, MASK / 2>(v, lane);
+// Few experts (E <= 16) on the matrix cores.  One workgroup of 8 wavefronts takes 16 tokens; a
+// wavefront multiplies every 8th K sub-tile of 32 (the eight waves read neighbouring 64-byte
+// pieces of the same 16 rows of x at the same time) with v_mfma_f32_16x16x32_bf16: x is the row
+// operand (lane l: token l%16, k = 8*(l/16)..+7, 16 bytes straight from the row), the packed
+// gate matrix the column operand (lane l: expert l%16, the same k: one 1 KiB block per sub-tile,
+// in lane order).  All loads of up to 16 sub-tiles are issued before the first multiply, so a
+// wave has 32 KiB in flight.  The eight partial sums of a logit meet in LDS and are added in
+// wave order; then wave r (r < 4) finishes tokens 4q + r, q = 0..3, all four at once: the 16
+// logits of a token sit in one row of 16 lanes, so max / sum / arg-max are four butterfly steps
+// inside a row, none through LDS.  No per-lane FMA loop and no cross-lane reduction of partial
+// sums: the matrix instruction adds over K.
+
+constexpr int ROUTE_MFMA_WAVES = 8;
+constexpr int ROUTE_MFMA_AHEAD = 16;   // sub-tiles whose loads a wave issues before its first multiply
+
+__device__ __forceinline__ float row16_max(float v) {
+    v = fmaxf(v, pair_f<1>(v));
+    v = fmaxf(v, pair_f<2>(v));
+    v = fmaxf(v, pair_f<4>(v));
+    v = fmaxf(v, pair_f<8>(v));
+    return v;
+}
+__device__ __forceinline__ float row16_sum(float v) {
+    v += pair_f<1>(v);
+    v += pair_f<2>(v);
+    v += pair_f<4>(v);
+    v += pair_f<8>(v);
+    return v;
 }
 
-// Few experts (E <= 16): HBM-bound.  One workgroup of 4 wavefronts takes TOK tokens; every wave
-// works on all TOK tokens but only on a quarter of the hidden dimension (thread i owns
-// h = 2048*it + 8*i .. +7), so a wave has TOK 16-byte loads in flight per step and reads a quarter
-// of Wg (8*E contiguous bf16 per 8 hidden elements, cache resident).  The per-lane partial sums
-// go through lane_reduce_scatter, the four waves' results through LDS (added in wave order), and
-// each wave then finishes TOK/4 tokens.  The sum that makes a logit does not depend on TOK, on
-// the token's slot in the workgroup or on T.
-template <int EP, bool EXACT, int TOK>  // EP: padded expert count (8 or 16); EXACT: E == EP, rows of Wg are 16-byte vectors
-__global__ __launch_bounds__(256) void route_small_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ wg,
-                                                          const float* __restrict__ bias, int T, int H, int E, int k,
-                                                          int renorm, float scale, int32_t* __restrict__ idx_out,
-                                                          float* __restrict__ w_out, float* __restrict__ logits_out) {
-    constexpr int NVAL = TOK * EP;   // 64 or 128
-    constexpr int PER = NVAL / 64;
-    static_assert(NVAL == 64 || NVAL == 128, "lane_reduce_scatter needs 64 or 128 values");
-    __shared__ float part[4][NVAL];
-    __shared__ float logit_s[NVAL];
+__global__ __launch_bounds__(ROUTE_MFMA_WAVES * 64) void route_mfma_kernel(
+    const char* __restrict__ x, const char* __restrict__ wg_packed, const float* __restrict__ bias, int T, int H, int E, int k,
+    int renorm, float scale, int32_t* __restrict__ idx_out, float* __restrict__ w_out, float* __restrict__ logits_out) {
+    __shared__ float part[ROUTE_MFMA_WAVES][4][64];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int t0 = blockIdx.x * TOK;
-    float acc[NVAL];   // [token slot a][expert e] at a*EP + e
+    const int row = lane & 15, g = lane >> 4;
+    const int t0 = blockIdx.x * 16;
+    const char* xa = x + (size_t)min(t0 + row, T - 1) * H * 2 + g * 16;
+    const char* wb = wg_packed + row * 64 + ((g ^ block_swizzle(row)) << 4);
+    const int KS = H >> 5;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int ks0 = wave; ks0 < KS; ks0 += ROUTE_MFMA_WAVES * ROUTE_MFMA_AHEAD) {
+        bf16x8 a[ROUTE_MFMA_AHEAD], b[ROUTE_MFMA_AHEAD];
 #pragma unroll
-    for (int i = 0; i < NVAL; ++i) acc[i] = 0.f;
-    for (int h0 = threadIdx.x * 8; h0 < H; h0 += 2048) {
-        uint4 xv[TOK];
-#pragma unroll
-        for (int a = 0; a < TOK; ++a) {
-            const int t = min(t0 + a, T - 1);
-            xv[a] = *reinterpret_cast<const uint4*>(x + (size_t)t * H + h0);
-        }
-#pragma unroll
-        for (int hh = 0; hh < 8; ++hh) {
-            float xa[TOK];
-#pragma unroll
-            for (int a = 0; a < TOK; ++a) {
-                const uint32_t u = (&xv[a].x)[hh >> 1];
-                xa[a] = (hh & 1) ? __uint_as_float(u & 0xffff0000u) : __uint_as_float(u << 16);
-            }
-            const uint16_t* wr = wg + (size_t)(h0 + hh) * E;
-            float wv[EP];
-            if (EXACT) {
-#pragma unroll
-                for (int c = 0; c < EP / 8; ++c) {
-                    const uint4 q = reinterpret_cast<const uint4*>(wr)[c];
-                    const uint32_t u[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        wv[c * 8 + 2 * i] = __uint_as_float(u[i] << 16);
-                        wv[c * 8 + 2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u);
-                    }
-                }
+        for (int u = 0; u < ROUTE_MFMA_AHEAD; ++u) {
+            const int ks = ks0 + u * ROUTE_MFMA_WAVES;
+            if (ks < KS) {   // wave-uniform
+                a[u] = *reinterpret_cast<const bf16x8*>(xa + (size_t)ks * 64);
+                b[u] = *reinterpret_cast<const bf16x8*>(wb + (size_t)ks * 1024);
             } else {
 #pragma unroll
-                for (int e = 0; e < EP; ++e) wv[e] = e < E ? __uint_as_float((uint32_t)wr[e] << 16) : 0.f;
+                for (int q = 0; q < 8; ++q) { a[u][q] = (__bf16)0.0f; b[u][q] = (__bf16)0.0f; }
             }
-#pragma unroll
-            for (int e = 0; e < EP; ++e)
-#pragma unroll
-                for (int a = 0; a < TOK; ++a) acc[a * EP + e] = fmaf(xa[a], wv[e], acc[a * EP + e]);
         }
-    }
-    lane_reduce_scatter<NVAL>(acc, lane);
 #pragma unroll
-    for (int i = 0; i < PER; ++i) part[wave][lane * PER + i] = acc[i];
-    __syncthreads();
-    if (threadIdx.x < NVAL) {
-        const int i = threadIdx.x;
-        logit_s[i] = ((part[0][i] + part[1][i]) + part[2][i]) + part[3][i];
+        for (int u = 0; u < ROUTE_MFMA_AHEAD; ++u) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u], b[u], acc, 0, 0, 0);
     }
+    // acc[r]: token t0 + 4*g + r, expert `row` (partial over this wave's sub-tiles)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) part[wave][r][lane] = acc[r];
     __syncthreads();
-    for (int a = wave; a < TOK; a += 4) {
-        const int t = t0 + a;
-        if (t >= T) break;  // wave-uniform; no barrier follows
-        float mine = -INFINITY;
-        if (lane < E) mine = logit_s[a * EP + lane] + (bias ? bias[lane] : 0.f);
-        const float v[1] = {mine};
-        route_finish<1>(v, lane, t, E, k, renorm, scale, idx_out, w_out, logits_out);
+    if (wave >= 4) return;   // wave-uniform; no barrier follows
+    const int r = wave;
+    float v = 0.f;
+#pragma unroll
+    for (int w8 = 0; w8 < ROUTE_MFMA_WAVES; ++w8) v += part[w8][r][lane];
+    const int tok = t0 + 4 * g + r;
+    const bool valid = tok < T;
+    const int e = row;
+    v = e < E ? v + (bias ? bias[e] : 0.f) : -INFINITY;
+    if (logits_out && valid && e < E) logits_out[(size_t)tok * E + e] = v;
+    const float m = row16_max(v);
+    const float p = expf(v - m);   // exp(-inf) = 0 for padded experts
+    const float rz = 1.0f / row16_sum(p);
+    float my_w = 0.f;
+    int my_e = 0;
+    bool taken = false;
+    for (int j = 0; j < k; ++j) {
+        float bv = taken ? -INFINITY : v, bp = p;
+        int be = (taken || e >= E) ? 0x7fffffff : e;
+        auto step = [&](auto m_tag) __attribute__((always_inline)) {
+            constexpr int M = decltype(m_tag)::value;
+            const float ov = pair_f<M>(bv);
+            const int oe = pair_i<M>(be);
+            const float op = pair_f<M>(bp);
+            // (value, -id) is a total order over the lanes that still hold a candidate
+            if (oe != 0x7fffffff && (be == 0x7fffffff || ov > bv || (ov == bv && oe < be))) { bv = ov; be = oe; bp = op; }
+        };
+        step(std::integral_constant<int, 1>{});
+        step(std::integral_constant<int, 2>{});
+        step(std::integral_constant<int, 4>{});
+        step(std::integral_constant<int, 8>{});
+        if (row == j) { my_e = be; my_w = bp * rz; }
+        if (e == be) taken = true;
+    }
+    const float wsum = row16_sum(row < k ? my_w : 0.f);
+    if (valid && row < k) {
+        float wv = my_w;
+        if (renorm) wv = wv / wsum;
+        idx_out[(size_t)tok * k + row] = my_e;
+        w_out[(size_t)tok * k + row] = wv * scale;
     }
 }
 
@@ -266,30 +276,11 @@ hipError_t launch_route_topk(const moe_shape& s, const float* partial, int split
     return hipGetLastError();
 }
 
-hipError_t launch_route(const moe_shape& s, const void* x, const void* wg, const float* bias, int32_t* idx,
-                        float* w, float* logits, hipStream_t st) {
-    if (s.E <= 16) {
-        // Tokens per workgroup: as many as the registers hold (16 with 8 experts, 8 with 16) when
-        // that still gives every CU two workgroups, else half of that.
-        const bool big = s.T >= 2 * 256 * (s.E <= 8 ? 16 : 8);
-#define ROUTE_SMALL(EP_, EX_, TOK_)                                                                                 \
-    hipLaunchKernelGGL((route_small_kernel<EP_, EX_, TOK_>), dim3((s.T + TOK_ - 1) / TOK_), dim3(256), 0, st,          \
-                       (const uint16_t*)x, (const uint16_t*)wg, bias, s.T, s.H, s.E, s.top_k, s.renormalize,          \
-                       s.routed_scale, idx, w, logits)
-#define ROUTE_SMALL_T(EP_, EX_, TB_, TS_)      \
-    do {                                       \
-        if (big) ROUTE_SMALL(EP_, EX_, TB_);   \
-        else ROUTE_SMALL(EP_, EX_, TS_);       \
-    } while (0)
-        if (s.E == 8) ROUTE_SMALL_T(8, true, 16, 8);
-        else if (s.E < 8) ROUTE_SMALL_T(8, false, 16, 8);
-        else if (s.E == 16) ROUTE_SMALL_T(16, true, 8, 4);
-        else ROUTE_SMALL_T(16, false, 8, 4);
-#undef ROUTE_SMALL_T
-#undef ROUTE_SMALL
-        return hipGetLastError();
-    }
-    return hipErrorInvalidValue;  // E > 16 goes through the GEMM path (launch_route_plan / launch_route_topk)
+hipError_t launch_route_mfma(const moe_shape& s, const void* x, const void* wg_packed, const float* bias, int32_t* idx,
+                             float* w, float* logits, hipStream_t st) {
+    hipLaunchKernelGGL(route_mfma_kernel, dim3((s.T + 15) / 16), dim3(ROUTE_MFMA_WAVES * 64), 0, st, (const char*)x,
+                       (const char*)wg_packed, bias, s.T, s.H, s.E, s.top_k, s.renormalize, s.routed_scale, idx, w, logits);
+    return hipGetLastError();
 }
 
 }  // namespace moe

@@ -73,24 +73,22 @@ def test_route(moe, name, over):
     moe.route(shape, li.x, li.wg, bias, idx2, w2, None, ws)
     torch.cuda.synchronize()
     assert torch.equal(idx, idx2) and torch.equal(w, w2)
-    # a gate matrix packed once by the caller (E > 16 only) gives the same bits as packing per call
+    # a gate matrix packed once by the caller gives the same bits as packing per call
     wgp = moe.pack_gate(shape, li.wg)
-    assert (wgp is None) == (cfg.E <= 16)
-    if wgp is not None:
-        ws2 = torch.full_like(ws, 0x5A)          # nothing may be read from the workspace's gate region
-        idx3 = torch.empty_like(idx); w3 = torch.empty_like(w)
-        moe.set_option("gate_packed", 1)
-        try:
-            moe.route(shape, li.x, wgp, bias, idx3, w3, None, ws2)
-            torch.cuda.synchronize()
-        finally:
-            moe.set_option("gate_packed", 0)
-        assert torch.equal(idx, idx3) and torch.equal(w, w3)
+    ws2 = torch.full_like(ws, 0x5A)          # nothing may be read from the workspace's gate region
+    idx3 = torch.empty_like(idx); w3 = torch.empty_like(w)
+    moe.set_option("gate_packed", 1)
+    try:
+        moe.route(shape, li.x, wgp, bias, idx3, w3, None, ws2)
+        torch.cuda.synchronize()
+    finally:
+        moe.set_option("gate_packed", 0)
+    assert torch.equal(idx, idx3) and torch.equal(w, w3)
 
 
-def test_route_exact_ties_pick_lowest_expert(moe):
+@pytest.mark.parametrize("T,H,E,k", [(40, 64, 70, 3), (40, 64, 16, 16), (21, 128, 8, 2), (33, 64, 5, 5), (1, 64, 1, 1)])
+def test_route_exact_ties_pick_lowest_expert(moe, T, H, E, k):
     from paper_2503_09716_amd import make_shape
-    T, H, E, k = 40, 64, 70, 3
     x = normal_bf16(1, 0, (T, H), 1.0, "cuda")
     wg = torch.zeros((H, E), dtype=torch.bfloat16, device="cuda")
     idx = torch.empty((T, k), dtype=torch.int32, device="cuda")
@@ -118,7 +116,7 @@ def random_routing(rng, T, E, k, skew=None):
     return idx
 
 
-# One launch up to 4096 pairs, beyond that histogram / scan / placement are three launches
+# One launch up to 4096 pairs, beyond that two (histogram; scan + placement), three when the table of histograms is large
 PERMUTE_CASES = [(256, 8, 2, None), (1000, 64, 6, None), (777, 160, 6, "one"), (1, 4, 1, None), (300, 5, 5, None),
                  (2049, 37, 3, None), (682, 256, 6, None), (683, 256, 6, None), (500, 160, 6, "one"), (12000, 37, 6, "one"),
                  (32768, 8, 2, None), (16384, 16, 4, None), (16385, 16, 4, None), (4099, 13, 3, "one"), (1025, 17, 4, None),
