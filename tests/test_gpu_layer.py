@@ -39,6 +39,8 @@ SMALL = [
     ("C1", dict(T=1, H=64, F=64, E=4, top_k=2)),             # one token, smallest widths
     ("C4", dict(T=96, H=64, F=64, E=254, top_k=32, num_shared=2)),   # E + shared = 256 groups, wide top-k
     ("C4", dict(T=70, H=128, F=64, E=8, top_k=8, num_shared=8)),     # k = E, 8 shared experts
+    ("C2", dict(T=2500, H=256, F=256)),                      # few experts, > 4096 pairs (two-launch permutation), token count not a multiple of 16
+    ("C3", dict(T=4100, H=128, F=128, E=16, top_k=4)),       # the same with 16 experts, a gate bias and a last router workgroup of 4 tokens
 ]
 
 
