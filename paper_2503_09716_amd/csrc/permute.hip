@@ -190,7 +190,7 @@ __global__ __launch_bounds__(256) void permute_index_fused_kernel(const int32_t*
     __shared__ unsigned long long mask[4][MAX_E];  // [wave][expert]: lanes of that wave that picked the expert
     __shared__ int cur[MAX_E];
     __shared__ int wave_sum[4];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, chunk = blockIdx.x;
+    const int tid = threadIdx.x, wave = tid >> 6, chunk = blockIdx.x;
     for (int i = tid; i < 4 * 2 * MAX_E; i += 256) (&hist[0][0][0])[i] = 0;
     for (int i = tid; i < 4 * MAX_E; i += 256) (&mask[0][0])[i] = 0ull;
     __syncthreads();
