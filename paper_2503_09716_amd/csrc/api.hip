@@ -114,7 +114,22 @@ RouteGemm route_gemm_config(const moe_shape& s) {
     RouteGemm r{0, 0, 0};
     r.ep = (s.E + 31) & ~31;   // rows of the packed gate matrix (zero rows past E)
     if (s.E <= 16) return r;   // splits = 0: no gate GEMM launch, route_mfma_kernel does it all
-    r.splits = (s.H % 256 == 0 && s.H >= 1024) ? 4 : (s.H % 128 == 0 ? 2 : 1);
+    // K pieces: a divisor of H/32 (a piece is a whole number of K sub-tiles, at least two), at most 8:
+    // the smallest that keeps a chain of fp32 additions at or under 1536 terms (the logits'
+    // rounding error grows with the chain: a single chain over H = 6336 measured 7e-6 against
+    // the fp64 reference, over half the near-tie margin), and from H = 1024 on at least 4
+    // (enough tiles to fill the chip at the batch sizes this is for).  If no divisor reaches that
+    // count, the largest one below it.
+    const int kt = s.H / 32;
+    int want = (s.H + 1535) / 1536;
+    if (s.H >= 1024 && want < 4) want = 4;
+    int below = 1, pick = 0;
+    for (int n = 1; n <= 8 && !pick; ++n) {
+        if (kt % n != 0 || kt / n < 2) continue;
+        if (n >= want) pick = n;
+        else below = n;
+    }
+    r.splits = pick ? pick : below;
     r.tm = (int64_t)r.splits * ((s.T + 255) / 256) >= 512 ? 256 : 128;
     return r;
 }

@@ -38,8 +38,13 @@ ROUTE_CASES = [
     ("C3", dict(T=50, H=64, E=12, top_k=3)),
     ("C1", dict(T=9, H=1088, E=1, top_k=1)),
     ("C4", dict(T=700, H=1024)),                  # matrix-core path, 4 K-splits
-    ("C5", dict(T=300, H=384)),                   # 2 K-splits, 160 experts padded to 160
-    ("C5", dict(T=130, H=192, E=17, top_k=5)),    # 1 K-split, 17 experts padded to 32
+    ("C5", dict(T=300, H=384)),                   # 1 K-split, 160 experts padded to 160
+    ("C5", dict(T=130, H=192, E=17, top_k=5)),    # 17 experts padded to 32
+    ("C5", dict(T=200, H=1088, E=40, top_k=6)),   # H/32 = 34: 2 K-splits of 17 sub-tiles
+    ("C4", dict(T=300, H=3520)),                  # H/32 = 110: 5 K-splits (a single chain this long misses the logit bar)
+    ("C5", dict(T=260, H=6336, E=163, top_k=8)),  # H/32 = 198: 6 K-splits of 33 sub-tiles
+    ("C4", dict(T=130, H=7168, E=33, top_k=4)),   # 7 K-splits
+    ("C4", dict(T=140, H=4544, E=74, top_k=5)),   # H/32 = 2 * 71: 2 K-splits of 2272 terms, the longest chains in use
     ("C3", dict(T=64, H=128, E=256, top_k=8)),
     ("C4", dict(T=50, H=64, E=256, top_k=64, num_shared=0)),    # the largest expert count and k the library accepts
     ("C5", dict(T=1, H=64, E=160, top_k=6)),      # a single token through the matrix-core path
