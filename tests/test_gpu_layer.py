@@ -360,7 +360,7 @@ def test_layer_in_a_hip_graph(moe):
         assert torch.equal(eager, ref)
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(int(os.environ.get("MOE_FUZZ_SEEDS", "24"))))
 def test_layer_random_small_shapes(moe, seed):
     """Seeded random shapes (ragged T, odd expert counts, k up to E, 0-3 shared experts, widths
     that are odd multiples of 64) through moe_layer, every token against the oracle."""

@@ -1,5 +1,7 @@
 """GPU parity of each staged C-ABI call against the CPU oracle, element by element, at sizes
 the oracle finishes in seconds but that span several tiles and ragged tails."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -17,6 +19,10 @@ def moe():
     m = Moe(0)
     yield m
     m.close()
+
+
+# Seeded random cases per sweep below; MOE_FUZZ_SEEDS=400 runs the long version (a minute or two on the GPU).
+FUZZ_SEEDS = int(os.environ.get("MOE_FUZZ_SEEDS", "48"))
 
 
 def say(*a):
@@ -105,6 +111,32 @@ def test_route_exact_ties_pick_lowest_expert(moe, T, H, E, k):
     np.testing.assert_allclose(w.cpu().numpy(), 1.0 / E, rtol=1e-6)
 
 
+@pytest.mark.parametrize("seed", range(FUZZ_SEEDS))
+def test_route_random_shapes(moe, seed):
+    """Seeded random router shapes (T up to 9000, H up to 6336 in steps of 64, 1..256 experts, k up to 16, the
+    three kinds of gate bias): selection against the oracle, logits within 5e-6."""
+    from paper_2503_09716_amd import shape_of
+    rng = np.random.default_rng(91000 + seed)
+    E = int(rng.integers(1, 17)) if seed % 3 else int(rng.integers(17, 257))
+    k = int(rng.integers(1, min(E, 16) + 1))
+    cfg = scaled_config(["C2", "C3", "C4", "C5"][seed % 4], T=int(rng.integers(1, 9000)), H=64 * int(rng.integers(1, 100)),
+                        E=E, top_k=k, bias=["none", "normal", "logzipf_rank"][seed % 3])
+    say("route fuzz", seed, cfg.T, cfg.H, E, k, cfg.bias, cfg.renormalize)
+    li = make_layer_inputs(cfg, device="cuda", experts=False)
+    shape = shape_of(cfg)
+    idx = torch.empty((cfg.T, k), dtype=torch.int32, device="cuda")
+    w = torch.empty((cfg.T, k), dtype=torch.float32, device="cuda")
+    logits = torch.empty((cfg.T, E), dtype=torch.float32, device="cuda")
+    bias = None if li.bias is None else torch.from_numpy(li.bias).cuda()
+    moe.route(shape, li.x, li.wg, bias, idx, w, logits, moe.new_workspace(shape))
+    torch.cuda.synchronize()
+    ref = orc.route(torch_bf16_to_u16(li.x), torch_bf16_to_u16(li.wg), li.bias, k, cfg.renormalize, cfg.routed_scale,
+                    want_logits=True, want_probs=True)
+    say(P.compare_routing(idx.cpu().numpy(), w.cpu().numpy(), ref, k, cfg.renormalize, cfg.routed_scale))
+    err = np.abs(logits.cpu().numpy() - ref["logits"]).max()
+    assert err < 5e-6, err
+
+
 def random_routing(rng, T, E, k, skew=None):
     """Distinct experts per token.  skew = 'one': expert 0 stays empty, every token goes to expert 1,
     and the top third of the expert ids is hit by a single token each (tiny groups)."""
@@ -129,13 +161,9 @@ PERMUTE_CASES = [(256, 8, 2, None), (1000, 64, 6, None), (777, 160, 6, "one"), (
                  (16384, 256, 1, None), (16385, 256, 1, None)]
 
 
-@pytest.mark.parametrize("T,E,k,skew", PERMUTE_CASES)
-def test_permute(moe, T, E, k, skew):
+def check_permute(moe, T, E, k, idx_h, H=128):
+    """moe_permute on the given routing against the oracle's stable counting sort, bit for bit."""
     from paper_2503_09716_amd import make_shape
-    say("permute", T, E, k, skew)
-    H = 128
-    rng = np.random.default_rng(T * 7 + E)
-    idx_h = random_routing(rng, T, E, k, skew)
     shape = make_shape(T, H, 64, E, k)
     x = normal_bf16(3, 0, (T, H), 1.0, "cuda")
     idx = torch.from_numpy(idx_h).cuda()
@@ -157,6 +185,28 @@ def test_permute(moe, T, E, k, skew):
     np.testing.assert_array_equal(torch_bf16_to_u16(x_perm), xh[o_perm // k])
     # every token appears exactly k times
     np.testing.assert_array_equal(np.bincount(perm.cpu().numpy() // k, minlength=T), np.full(T, k))
+
+
+@pytest.mark.parametrize("T,E,k,skew", PERMUTE_CASES)
+def test_permute(moe, T, E, k, skew):
+    say("permute", T, E, k, skew)
+    rng = np.random.default_rng(T * 7 + E)
+    check_permute(moe, T, E, k, random_routing(rng, T, E, k, skew))
+
+
+@pytest.mark.parametrize("seed", range(FUZZ_SEEDS))
+def test_permute_random_shapes(moe, seed):
+    """Seeded random shapes across the one-, two- and three-launch paths (1..70000 tokens, 1..256 experts,
+    k up to 8; uniform routing, one expert taking every token, or everything on k + 1 experts)."""
+    rng = np.random.default_rng(55000 + seed)
+    E = int(rng.integers(1, 257))
+    k = int(rng.integers(1, min(E, 8) + 1))
+    T = int([rng.integers(1, 600), rng.integers(600, 20000), rng.integers(20000, 70000)][seed % 3])
+    idx_h = random_routing(rng, T, E, k, "one" if (seed % 5 == 0 and E >= 6) else None)
+    if seed % 7 == 0 and k < E:
+        idx_h = np.stack([(np.arange(k) + (t % 2)) % E for t in range(T)]).astype(np.int32)
+    say("permute fuzz", seed, T, E, k)
+    check_permute(moe, T, E, k, idx_h, H=64)
 
 
 def run_ffn_stage(moe, cfg, idx_h, wave_rows=2, small_tiles=1, use_row_token=False, y_fp32=True, waves=4):
