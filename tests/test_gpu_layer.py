@@ -25,6 +25,11 @@ def moe():
     m.close()
 
 
+def fuzz_seeds(default):
+    """Seeds of a random-shape sweep: `default` of them, or MOE_FUZZ_SEEDS for the long version."""
+    return range(int(os.environ.get("MOE_FUZZ_SEEDS", default)))
+
+
 def say(*a):
     print(*a, flush=True)
 
@@ -360,7 +365,7 @@ def test_layer_in_a_hip_graph(moe):
         assert torch.equal(eager, ref)
 
 
-@pytest.mark.parametrize("seed", range(int(os.environ.get("MOE_FUZZ_SEEDS", "24"))))
+@pytest.mark.parametrize("seed", fuzz_seeds(24))
 def test_layer_random_small_shapes(moe, seed):
     """Seeded random shapes (ragged T, odd expert counts, k up to E, 0-3 shared experts, widths
     that are odd multiples of 64) through moe_layer, every token against the oracle."""
@@ -392,7 +397,7 @@ def test_layer_short_shared_tail_next_to_k_split_tails(moe, T, F, E, Ns):
     say(json.dumps(P.check_layer_against_oracle(gl, out, out16=out16)))
 
 
-@pytest.mark.parametrize("seed", range(12))
+@pytest.mark.parametrize("seed", fuzz_seeds(12))
 def test_layer_random_k_split_shapes(moe, seed):
     """Seeded random shapes inside the K-split-tail regime (E <= 32, F a multiple of 128 from 512
     up), with and without shared experts, every token against the oracle."""
@@ -413,7 +418,7 @@ OPTION_DEFAULTS = {"tails_last": -1, "gemm_group_m": 0, "xcd_remap": 1, "x_tiled
                    "gemm_tile_rows_up": 0, "gemm_tile_rows_down": 0, "gemm_waves": 4, "gemm_wave_rows": 1, "tall_tiles": -1}
 
 
-@pytest.mark.parametrize("seed", range(48))
+@pytest.mark.parametrize("seed", fuzz_seeds(48))
 def test_layer_fuzz_entry_points_and_options(moe, seed):
     """One seeded random shape per case (half of them inside the K-split-tail regime):
     (1) moe_layer against the oracle, every token;
@@ -471,7 +476,7 @@ def test_layer_fuzz_entry_points_and_options(moe, seed):
         moe.set_option("out_fp32", 0)
 
 
-@pytest.mark.parametrize("seed", range(16))
+@pytest.mark.parametrize("seed", fuzz_seeds(16))
 def test_staged_calls_fuzz_equal_fused_layer(moe, seed):
     """moe_route -> moe_permute -> moe_grouped_ffn -> moe_combine on seeded random shapes give the
     bits of moe_layer (y_perm in fp32 on both sides), with the rows either gathered into x_perm
