@@ -159,6 +159,71 @@ __device__ __forceinline__ float row16_sum(float v) {
     return v;
 }
 
+// Softmax over all experts + top-k (k <= 16) for the token held by one ROW of 16 lanes: the lane
+// with row index c holds the logits of experts c, c+16, ... in v[] (-inf past E); a wavefront
+// finishes four tokens at once.  Max, sum and the k arg-max rounds (ties -> lower expert id, on
+// the logits, so rounding in exp / division can never change the selection) are four butterfly
+// steps inside the row, all on the VALU's DPP path.  Lane j of the row ends up with the j-th pick.
+template <int NV>
+__device__ __forceinline__ void route_finish_row16(const float (&v)[NV], const int row, const int tok, const bool valid,
+                                                   const int E, const int k, const int renorm, const float scale,
+                                                   int32_t* __restrict__ idx_out, float* __restrict__ w_out,
+                                                   float* __restrict__ logits_out) {
+    float p[NV];
+    float m = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int e = row + 16 * i;
+        m = fmaxf(m, v[i]);
+        if (logits_out && valid && e < E) logits_out[(size_t)tok * E + e] = v[i];
+    }
+    m = row16_max(m);
+    float z = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        p[i] = expf(v[i] - m);   // exp(-inf) = 0 for padded experts
+        z += p[i];
+    }
+    const float rz = 1.0f / row16_sum(z);
+    float my_w = 0.f;
+    int my_e = 0;
+    unsigned taken = 0;
+    for (int j = 0; j < k; ++j) {
+        // lane-local best among the not-yet-selected (ascending expert id, strict >)
+        float bv = -INFINITY, bp = 0.f;
+        int be = 0x7fffffff;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int e = row + 16 * i;
+            const bool ok = e < E && !((taken >> i) & 1u);
+            if (ok && (be == 0x7fffffff || v[i] > bv)) { bv = v[i]; be = e; bp = p[i]; }
+        }
+        auto step = [&](auto m_tag) __attribute__((always_inline)) {
+            constexpr int M = decltype(m_tag)::value;
+            const float ov = pair_f<M>(bv);
+            const int oe = pair_i<M>(be);
+            const float op = pair_f<M>(bp);
+            // (value, -id) is a total order over the lanes that still hold a candidate
+            if (oe != 0x7fffffff && (be == 0x7fffffff || ov > bv || (ov == bv && oe < be))) { bv = ov; be = oe; bp = op; }
+        };
+        step(std::integral_constant<int, 1>{});
+        step(std::integral_constant<int, 2>{});
+        step(std::integral_constant<int, 4>{});
+        step(std::integral_constant<int, 8>{});
+        if (row == j) { my_e = be; my_w = bp * rz; }
+#pragma unroll
+        for (int i = 0; i < NV; ++i)
+            if (row + 16 * i == be) taken |= 1u << i;
+    }
+    const float wsum = row16_sum(row < k ? my_w : 0.f);
+    if (valid && row < k) {
+        float wv = my_w;
+        if (renorm) wv = wv / wsum;
+        idx_out[(size_t)tok * k + row] = my_e;
+        w_out[(size_t)tok * k + row] = wv * scale;
+    }
+}
+
 __global__ __launch_bounds__(ROUTE_MFMA_WAVES * 64) void route_mfma_kernel(
     const char* __restrict__ x, const char* __restrict__ wg_packed, const float* __restrict__ bias, int T, int H, int E, int k,
     int renorm, float scale, int32_t* __restrict__ idx_out, float* __restrict__ w_out, float* __restrict__ logits_out) {
@@ -197,41 +262,8 @@ __global__ __launch_bounds__(ROUTE_MFMA_WAVES * 64) void route_mfma_kernel(
 #pragma unroll
     for (int w8 = 0; w8 < ROUTE_MFMA_WAVES; ++w8) v += part[w8][r][lane];
     const int tok = t0 + 4 * g + r;
-    const bool valid = tok < T;
-    const int e = row;
-    v = e < E ? v + (bias ? bias[e] : 0.f) : -INFINITY;
-    if (logits_out && valid && e < E) logits_out[(size_t)tok * E + e] = v;
-    const float m = row16_max(v);
-    const float p = expf(v - m);   // exp(-inf) = 0 for padded experts
-    const float rz = 1.0f / row16_sum(p);
-    float my_w = 0.f;
-    int my_e = 0;
-    bool taken = false;
-    for (int j = 0; j < k; ++j) {
-        float bv = taken ? -INFINITY : v, bp = p;
-        int be = (taken || e >= E) ? 0x7fffffff : e;
-        auto step = [&](auto m_tag) __attribute__((always_inline)) {
-            constexpr int M = decltype(m_tag)::value;
-            const float ov = pair_f<M>(bv);
-            const int oe = pair_i<M>(be);
-            const float op = pair_f<M>(bp);
-            // (value, -id) is a total order over the lanes that still hold a candidate
-            if (oe != 0x7fffffff && (be == 0x7fffffff || ov > bv || (ov == bv && oe < be))) { bv = ov; be = oe; bp = op; }
-        };
-        step(std::integral_constant<int, 1>{});
-        step(std::integral_constant<int, 2>{});
-        step(std::integral_constant<int, 4>{});
-        step(std::integral_constant<int, 8>{});
-        if (row == j) { my_e = be; my_w = bp * rz; }
-        if (e == be) taken = true;
-    }
-    const float wsum = row16_sum(row < k ? my_w : 0.f);
-    if (valid && row < k) {
-        float wv = my_w;
-        if (renorm) wv = wv / wsum;
-        idx_out[(size_t)tok * k + row] = my_e;
-        w_out[(size_t)tok * k + row] = wv * scale;
-    }
+    const float one[1] = {row < E ? v + (bias ? bias[row] : 0.f) : -INFINITY};
+    route_finish_row16<1>(one, row, tok, tok < T, E, k, renorm, scale, idx_out, w_out, logits_out);
 }
 
 // E > 16: the logits come from the grouped-GEMM tile routine (x row-major against the packed
@@ -260,10 +292,51 @@ __global__ __launch_bounds__(256) void route_topk_kernel(const float* __restrict
     route_finish<NV>(v, lane, t, E, k, renorm, scale, idx_out, w_out, logits_out);
 }
 
+// The same for k <= 16 with a token's logits in a row of 16 lanes (lane c: experts c, c+16, ...):
+// four tokens per wavefront, no step through the LDS crossbar.
+template <int NV>
+__global__ __launch_bounds__(256) void route_topk_row16_kernel(const float* __restrict__ partial, int splits, int T, int EP,
+                                                               int E, int k, const float* __restrict__ bias, int renorm,
+                                                               float scale, int32_t* __restrict__ idx_out,
+                                                               float* __restrict__ w_out, float* __restrict__ logits_out) {
+    const int lane = threadIdx.x & 63, row = lane & 15;
+    const int tok = (blockIdx.x * 4 + (threadIdx.x >> 6)) * 4 + (lane >> 4);
+    const int t = min(tok, T - 1);   // rows past the end redo the last token and write nothing
+    float v[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int e = row + 16 * i;
+        v[i] = -INFINITY;
+        if (e < E) {
+            float a = 0.f;
+            for (int s = 0; s < splits; ++s) a += partial[((size_t)s * T + t) * EP + e];
+            v[i] = a + (bias ? bias[e] : 0.f);
+        }
+    }
+    route_finish_row16<NV>(v, row, tok, tok < T, E, k, renorm, scale, idx_out, w_out, logits_out);
+}
+
 }  // namespace
 
 hipError_t launch_route_topk(const moe_shape& s, const float* partial, int splits, int ep, const float* bias,
                              int32_t* idx, float* w, float* logits, hipStream_t st) {
+    if (s.top_k <= 16) {
+        const dim3 grid((s.T + 15) / 16), block(256);
+#define TOPK16(NV_)                                                                                                 \
+    hipLaunchKernelGGL(route_topk_row16_kernel<NV_>, grid, block, 0, st, partial, splits, s.T, ep, s.E, s.top_k, bias, \
+                       s.renormalize, s.routed_scale, idx, w, logits)
+        const int nv = (s.E + 15) / 16;
+        if (nv <= 2) TOPK16(2);
+        else if (nv <= 4) TOPK16(4);
+        else if (nv <= 6) TOPK16(6);
+        else if (nv <= 8) TOPK16(8);
+        else if (nv <= 10) TOPK16(10);
+        else if (nv <= 12) TOPK16(12);
+        else if (nv <= 14) TOPK16(14);
+        else TOPK16(16);
+#undef TOPK16
+        return hipGetLastError();
+    }
     const dim3 grid((s.T + 3) / 4), block(256);
 #define TOPK(NV_)                                                                                              \
     hipLaunchKernelGGL(route_topk_kernel<NV_>, grid, block, 0, st, partial, splits, s.T, ep, s.E, s.top_k, bias,  \
