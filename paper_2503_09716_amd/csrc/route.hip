@@ -164,7 +164,13 @@ __device__ __forceinline__ float row16_sum(float v) {
 // finishes four tokens at once.  Max, sum and the k arg-max rounds (ties -> lower expert id, on
 // the logits, so rounding in exp / division can never change the selection) are four butterfly
 // steps inside the row, all on the VALU's DPP path.  Lane j of the row ends up with the j-th pick.
-template <int NV>
+// WIDE: the lane holds experts 4c..4c+3, 64+4c..64+4c+3, ... instead (what 16-byte loads of a
+// row of logits deliver); either way its experts ascend with i.
+template <bool WIDE>
+__device__ __forceinline__ int row16_expert(const int row, const int i) {
+    return WIDE ? row * 4 + (i & 3) + 64 * (i >> 2) : row + 16 * i;
+}
+template <int NV, bool WIDE = false>
 __device__ __forceinline__ void route_finish_row16(const float (&v)[NV], const int row, const int tok, const bool valid,
                                                    const int E, const int k, const int renorm, const float scale,
                                                    int32_t* __restrict__ idx_out, float* __restrict__ w_out,
@@ -173,7 +179,7 @@ __device__ __forceinline__ void route_finish_row16(const float (&v)[NV], const i
     float m = -INFINITY;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-        const int e = row + 16 * i;
+        const int e = row16_expert<WIDE>(row, i);
         m = fmaxf(m, v[i]);
         if (logits_out && valid && e < E) logits_out[(size_t)tok * E + e] = v[i];
     }
@@ -194,7 +200,7 @@ __device__ __forceinline__ void route_finish_row16(const float (&v)[NV], const i
         int be = 0x7fffffff;
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
-            const int e = row + 16 * i;
+            const int e = row16_expert<WIDE>(row, i);
             const bool ok = e < E && !((taken >> i) & 1u);
             if (ok && (be == 0x7fffffff || v[i] > bv)) { bv = v[i]; be = e; bp = p[i]; }
         }
@@ -213,7 +219,7 @@ __device__ __forceinline__ void route_finish_row16(const float (&v)[NV], const i
         if (row == j) { my_e = be; my_w = bp * rz; }
 #pragma unroll
         for (int i = 0; i < NV; ++i)
-            if (row + 16 * i == be) taken |= 1u << i;
+            if (row16_expert<WIDE>(row, i) == be) taken |= 1u << i;
     }
     const float wsum = row16_sum(row < k ? my_w : 0.f);
     if (valid && row < k) {
@@ -292,9 +298,10 @@ __global__ __launch_bounds__(256) void route_topk_kernel(const float* __restrict
     route_finish<NV>(v, lane, t, E, k, renorm, scale, idx_out, w_out, logits_out);
 }
 
-// The same for k <= 16 with a token's logits in a row of 16 lanes (lane c: experts c, c+16, ...):
-// four tokens per wavefront, no step through the LDS crossbar.
-template <int NV>
+// The same for k <= 16 with a token's logits in a row of 16 lanes: four tokens per wavefront, no
+// step through the LDS crossbar.  Lane c of a row reads experts 4c..4c+3 of every 64 as one
+// 16-byte load per partial matrix (NB = blocks of 64 experts).
+template <int NB>
 __global__ __launch_bounds__(256) void route_topk_row16_kernel(const float* __restrict__ partial, int splits, int T, int EP,
                                                                int E, int k, const float* __restrict__ bias, int renorm,
                                                                float scale, int32_t* __restrict__ idx_out,
@@ -302,18 +309,17 @@ __global__ __launch_bounds__(256) void route_topk_row16_kernel(const float* __re
     const int lane = threadIdx.x & 63, row = lane & 15;
     const int tok = (blockIdx.x * 4 + (threadIdx.x >> 6)) * 4 + (lane >> 4);
     const int t = min(tok, T - 1);   // rows past the end redo the last token and write nothing
-    float v[NV];
+    float v[4 * NB];
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        const int e = row + 16 * i;
-        v[i] = -INFINITY;
-        if (e < E) {
-            float a = 0.f;
-            for (int s = 0; s < splits; ++s) a += partial[((size_t)s * T + t) * EP + e];
-            v[i] = a + (bias ? bias[e] : 0.f);
-        }
+    for (int b = 0; b < NB; ++b) {
+        const int e0 = row * 4 + 64 * b;
+        f32x4 a = {0.f, 0.f, 0.f, 0.f};
+        if (e0 < EP)   // EP is a multiple of 32: the four values are all inside the row or all outside
+            for (int s = 0; s < splits; ++s) a += *reinterpret_cast<const f32x4*>(partial + ((size_t)s * T + t) * EP + e0);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[4 * b + q] = e0 + q < E ? a[q] + (bias ? bias[e0 + q] : 0.f) : -INFINITY;
     }
-    route_finish_row16<NV>(v, row, tok, tok < T, E, k, renorm, scale, idx_out, w_out, logits_out);
+    route_finish_row16<4 * NB, true>(v, row, tok, tok < T, E, k, renorm, scale, idx_out, w_out, logits_out);
 }
 
 }  // namespace
@@ -322,18 +328,13 @@ hipError_t launch_route_topk(const moe_shape& s, const float* partial, int split
                              int32_t* idx, float* w, float* logits, hipStream_t st) {
     if (s.top_k <= 16) {
         const dim3 grid((s.T + 15) / 16), block(256);
-#define TOPK16(NV_)                                                                                                 \
-    hipLaunchKernelGGL(route_topk_row16_kernel<NV_>, grid, block, 0, st, partial, splits, s.T, ep, s.E, s.top_k, bias, \
+#define TOPK16(NB_)                                                                                                 \
+    hipLaunchKernelGGL(route_topk_row16_kernel<NB_>, grid, block, 0, st, partial, splits, s.T, ep, s.E, s.top_k, bias, \
                        s.renormalize, s.routed_scale, idx, w, logits)
-        const int nv = (s.E + 15) / 16;
-        if (nv <= 2) TOPK16(2);
-        else if (nv <= 4) TOPK16(4);
-        else if (nv <= 6) TOPK16(6);
-        else if (nv <= 8) TOPK16(8);
-        else if (nv <= 10) TOPK16(10);
-        else if (nv <= 12) TOPK16(12);
-        else if (nv <= 14) TOPK16(14);
-        else TOPK16(16);
+        if (s.E <= 64) TOPK16(1);
+        else if (s.E <= 128) TOPK16(2);
+        else if (s.E <= 192) TOPK16(3);
+        else TOPK16(4);
 #undef TOPK16
         return hipGetLastError();
     }
