@@ -342,9 +342,13 @@ def sweep(args):
         out = torch.empty((cfg.T, cfg.H), dtype=torch.bfloat16, device="cuda")
         bias = None if li.bias is None else torch.from_numpy(li.bias).cuda()
         tables = moe.tables(w1p, w3p, w2p)
-        for _ in range(2):
-            moe.layer(shape, li.x, li.wg, bias, w1p, w3p, w2p, out, ws, tables=tables)
-        torch.cuda.synchronize()
+        # untimed settling phase, as in the benchmark proper: after the idle stretches of the streamed
+        # runs the chip's clocks need some tens of milliseconds of this load to stop moving
+        t_end = time.perf_counter() + 0.25
+        while time.perf_counter() < t_end:
+            for _ in range(4):
+                moe.layer(shape, li.x, li.wg, bias, w1p, w3p, w2p, out, ws, tables=tables)
+            torch.cuda.synchronize()
         moe.profile_enable(True)
         moe.profile_read()
         for _ in range(args.steps):
