@@ -117,10 +117,15 @@ size_t moe_h_scratch_bytes(const moe_shape* shape);
  *   "tails_last"      -1|0|1  order of a GEMM's tiles: 1 or -1 (default) = every expert's short tail tile (at most
  *                             half a tile high) after all other tiles, longest first; 0 = behind its own
  *                             expert's tiles.  Same results bit for bit.
- *   "down_tail_splits" 0 | 1  1 (default): with at most 32 experts the down projection cuts the contraction range of
- *                             every short tail tile into 2 or 4 pieces run by different CUs and adds the fp32
- *                             partial sums afterwards in fixed order; 0: one piece.  Changes the summation
- *                             order of those rows only (not bit-identical between 0 and 1).
+ *   "down_tail_splits" 0|1|2  with at most 32 experts the down projection can cut the contraction range of an
+ *                             expert's short tail tile into 2 or 4 pieces run by different CUs and add the fp32
+ *                             partial sums afterwards in fixed order.  0: never; 2: every eligible tail;
+ *                             1 (default): where it pays, decided on the device from the call's tile counts
+ *                             (launches in which every tile is a short tail, i.e. a few tokens per expert, and
+ *                             launches many rounds of tiles long).  Cutting changes the summation order of
+ *                             those rows only: results are deterministic for given inputs and options, but not
+ *                             bit-identical between the three settings, nor, under 1, between calls that
+ *                             cover the same tokens in differently sized passes.
  *   "tall_tiles"    -1|0|1|2  an expert's tail of at most 64 rows joins its last full 256-row tile (a tile of up to
  *                             320 rows: 12-25 % more time for that tile) instead of costing a pass of its own
  *                             over the expert's weights; 4 waves x 1 wave row only.  2: the tall tile keeps its
@@ -219,7 +224,7 @@ moe_status moe_combine(moe_ctx* ctx, const moe_shape* shape, const void* y_perm,
  * batching accumulates for it (Sec. 4.2), on one stream: route -> permute (indices; the row gather is fused
  * into the first GEMM's loads, or done once into a tiled x_perm: option "x_tiled") -> grouped
  * FFN -> combine.  Same results as the staged
- * calls bit for bit.  All intermediates live in `workspace`.  out [T,H] is bf16, or fp32
+ * calls bit for bit (options alike).  All intermediates live in `workspace`.  out [T,H] is bf16, or fp32
  * under option "out_fp32" = 1. */
 moe_status moe_layer(moe_ctx* ctx, const moe_shape* shape, const void* x_bf16, const void* wg_bf16,
                      const float* gate_bias, const void* const* w1p, const void* const* w3p,
@@ -266,7 +271,10 @@ moe_status moe_layer_chunked(moe_ctx* ctx, const moe_shape* shape, const void* x
  * `experts_per_group` consecutive non-empty experts; group g is copied into staging slot
  * g % num_slots with hipMemcpyAsync on a stream the context owns while the GEMMs of earlier
  * groups run on `hip_stream`; events hand the slots back and forth.  The shared experts form
- * the last group.  Same kernels and same results as moe_layer, bit for bit.
+ * the last group.  Same kernels and same results as moe_layer, bit for bit (with option
+ * "down_tail_splits" at 0 or 2; under its default rule a pass over one group of experts and a
+ * pass over all of them may decide differently whether to cut a short tail, which changes the
+ * summation order of that tail's rows).
  *   host_w1p / host_w3p / host_w2p: host arrays of E+num_shared HOST pointers to packed
  *   matrices (H*F bf16 each, moe_pack_weight layout), in pinned memory for the copies to overlap
  *   slots: device buffer of num_slots * slot_bytes bytes; a slot must hold

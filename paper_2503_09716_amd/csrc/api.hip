@@ -379,7 +379,14 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
     // its smallest work items.
     const bool tl_up = c->gemm.tails_last != 0;
     const bool tl_down = c->gemm.tails_last != 0;
-    const int dsp = (tl_down && c->gemm.small_tiles && c->gemm.down_tail_splits != 0) ? down_tail_splits(s) : 1;
+    // K pieces for short tails of the down GEMM: the device-side plan decides from the real tile
+    // counts whether to cut (ffn_plan_kernel); here only what the shape alone rules out, which
+    // spares the launch of the reduction: tiny matrices (a launch costs more than it can save).
+    int dsp = (tl_down && c->gemm.small_tiles && c->gemm.down_tail_splits != 0) ? down_tail_splits(s) : 1;
+    if (c->gemm.down_tail_splits == 1 && (int64_t)s.F * s.H < ((int64_t)1 << 21)) dsp = 1;
+    // "many rounds" for the plan's rule: eight rounds of 256 tiles (at two to three rounds pieces
+    // measured +6 %, at four to five +-0, at thirteen -2 %)
+    const int split_rule_tiles = c->gemm.down_tail_splits == 2 ? 0 : (2048 + nt_down - 1) / nt_down;
     SplitTail* split_tails = (SplitTail*)(ws + L.split_tails);
     {
         StageTimer tm(c, st, MOE_STAGE_PLAN);
@@ -391,7 +398,8 @@ moe_status run_ffn(moe_ctx* c, const moe_shape& s, const void* x_perm, const int
         int tall = c->gemm.tall_tiles >= 0 ? c->gemm.tall_tiles : (per_expert <= 8.0 ? 2 : 1);
         if (!tall_kernel) tall = 0;
         HIP_TRY(c, launch_ffn_plan(s, offsets, tm_up, tm_down, tl_up, tl_down, c->gemm.small_tiles != 0, ps.e_lo, ps.e_hi,
-                                   ps.shared_on, dsp, tall, tall, split_tails, plan, descs_up, descs_down, st));
+                                   ps.shared_on, dsp, 4, split_rule_tiles, tall, tall, split_tails, plan, descs_up,
+                                   descs_down, st));
     }
     GemmArgs a;
     memset(&a, 0, sizeof(a));
@@ -604,7 +612,7 @@ moe_status moe_set_option(moe_ctx* c, const char* key, int32_t v) {
     if (!strcmp(key, "gemm_tile_rows_up") && (v == 0 || v == 128 || v == 256 || v == 320)) { c->gemm.tile_rows_up = v; return MOE_OK; }
     if (!strcmp(key, "gemm_tile_rows_down") && (v == 0 || v == 128 || v == 256 || v == 320)) { c->gemm.tile_rows_down = v; return MOE_OK; }
     if (!strcmp(key, "x_tiled") && v >= -1 && v <= 1) { c->gemm.x_tiled = v; return MOE_OK; }
-    if (!strcmp(key, "down_tail_splits") && (v == 0 || v == 1)) { c->gemm.down_tail_splits = v; return MOE_OK; }
+    if (!strcmp(key, "down_tail_splits") && v >= 0 && v <= 2) { c->gemm.down_tail_splits = v; return MOE_OK; }
     if (!strcmp(key, "tails_last") && v >= -1 && v <= 1) { c->gemm.tails_last = v; return MOE_OK; }
     if (!strcmp(key, "tall_tiles") && v >= -1 && v <= 2) { c->gemm.tall_tiles = v; return MOE_OK; }
     if (!strcmp(key, "y_fp32") && (v == 0 || v == 1)) { c->y_fp32 = v != 0; return MOE_OK; }

@@ -87,7 +87,8 @@ struct GemmConfig {
     int tile_rows_down;    // same for the down GEMM
     int x_tiled;           // moe_layer: 1 = gather x into a tiled x_perm first, 0 = gather inside GEMM 1, -1 = choose
     int tails_last;        // order of the m-tile lists: 1 = short tail tiles after all full tiles, 0 = in group order, -1 = choose
-    int down_tail_splits;  // 1: the down GEMM cuts the K range of short tail tiles into pieces (few experts only); 0: off
+    int down_tail_splits;  // the down GEMM cuts the K range of short tail tiles into pieces (few experts only): 0 off,
+                           // 1 where it pays (decided on the device from the tile counts), 2 always
     int tall_tiles;        // a tail of <= 64 rows joins its group's last full 256-row tile (4 waves x 1 wave row only):
                            // 0 off, 1 tall tiles after the run region, 2 in place, -1 choose
 };
@@ -130,8 +131,8 @@ hipError_t launch_permute_gather_tiled(const moe_shape& s, const void* x, const 
 // the lists cover routed experts [e_lo, e_hi) and, if shared_on, the shared experts
 hipError_t launch_ffn_plan(const moe_shape& s, const int32_t* offsets, int tm_up, int tm_down, bool tails_last_up,
                            bool tails_last_down, bool small_tiles, int e_lo, int e_hi, bool shared_on,
-                           int down_tail_splits, int tall_up, int tall_down, SplitTail* split_tails, PlanHeader* plan,
-                           TileDesc* descs_up, TileDesc* descs_down, hipStream_t st);
+                           int down_tail_splits, int split_max_blocks, int split_rule_tiles, int tall_up, int tall_down,
+                           SplitTail* split_tails, PlanHeader* plan, TileDesc* descs_up, TileDesc* descs_down, hipStream_t st);
 // y_perm rows of the split tails = sum over pieces of the fp32 partials, in y_perm's dtype
 hipError_t launch_split_tail_reduce(const moe_shape& s, const PlanHeader* plan, const SplitTail* tails, const float* partial,
                                     int splits, void* y_perm, bool y_fp32, hipStream_t st);

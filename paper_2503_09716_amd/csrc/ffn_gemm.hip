@@ -506,9 +506,16 @@ __device__ __forceinline__ bool pick_tile(const GemmArgs& p, const bool gated, T
         d.srow = -1 - s;
         return true;
     }
-    const int L = tile_order(blockIdx.x, gridDim.x, p.xcd_remap);
     const int count = gated ? p.plan->n_gate_up : p.plan->n_down;
     const int n_run = gated ? p.plan->n_run_up : p.plan->n_run_down;
+    // Only whole rounds of 256 REAL tiles are dealt to the XCDs in runs of 32 (the grid is an upper
+    // bound of the tile count, and how far the runs reach must not depend on it); the last,
+    // partial round keeps the hardware's own order, which spreads it over all eight XCDs.  In
+    // runs it would sit on the first few XCDs and leave the L2s and fabric links of the others
+    // idle: a launch of 128 tiles measured 251 us on four XCDs against 210 us on eight, the
+    // second of two rounds 6 % more; over the Mixtral-shaped layer from 1024 to 8192 tokens the
+    // gate/up GEMM is 0.7-2.6 % faster this way, the named workloads are unchanged.
+    const int L = tile_order(blockIdx.x, count * p.n_tiles, p.xcd_remap);
     const int run_positions = n_run * p.n_tiles;
     int mt;
     if (L < run_positions) {
@@ -610,7 +617,7 @@ __device__ __forceinline__ void block_scan3(int& a, int& b, int& c, int (&tot)[3
 __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict__ offsets, int T, int t_pad, int E, int Ns,
                                                        int tm_up, int tm_down, int tails_last_up, int tails_last_down,
                                                        int small_tiles, int e_lo, int e_hi, int shared_on, int down_splits,
-                                                       int tall_up, int tall_down,
+                                                       int split_max_blocks, int split_rule_tiles, int tall_up, int tall_down,
                                                        SplitTail* __restrict__ split_tails, PlanHeader* __restrict__ plan,
                                                        TileDesc* __restrict__ descs_up, TileDesc* __restrict__ descs_down) {
     __shared__ int wsum[4][3];
@@ -670,11 +677,31 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
         const int cnt[5] = {0, (tot[1] >> 10) & 1023, (tot[1] >> 20) & 1023, tot[2] & 1023, (tot[2] >> 10) & 1023};
         const int pre[5] = {0, (k2 >> 10) & 1023, (k2 >> 20) & 1023, k3 & 1023, (k3 >> 10) & 1023};
         const int tails = cnt[1] + cnt[2] + cnt[3] + cnt[4];
+        // Down list with K pieces: only the moved tails of at most split_max_blocks 32-row blocks are
+        // cut (down_splits list entries each); the higher ones, which come first, stay whole.
+        // Whether to cut at all is decided here, where the tile counts are known.  Pieces make a
+        // launch faster in two cases only (measured on the Mixtral-shaped layer from 64 to 16384
+        // tokens): when EVERY tile of the launch is a short tail (a few tokens per expert: the
+        // pieces then shorten the longest tile and fill idle CUs, -10 %), and when the launch is
+        // many rounds of tiles long (the tails at its end then finish sooner: -2 % on the
+        // 16384-token, skewed workload).  In between, a launch of one to three rounds is as long
+        // as its full tiles whatever happens to the tails, and pieces only add a round and
+        // traffic (+6 ... +50 % measured).  split_rule_tiles: that many m-tiles or more count as
+        // "many rounds"; 0: always cut.
+        int n_whole = tails;
+        bool cutting = which == 1 && down_splits > 1;
+        if (cutting) {
+            n_whole = 0;
+            for (int b = split_max_blocks + 1; b <= 4; ++b) n_whole += cnt[b];
+            const int others = n_run_s + n_tall_s + n_whole;
+            cutting = split_rule_tiles == 0 || others == 0 || others + tails - n_whole >= split_rule_tiles;
+            if (!cutting) n_whole = tails;
+        }
+        const int n_cut = tails - n_whole;
         if (tid == 0) {
-            const int per_tail = which == 1 ? down_splits : 1;   // list entries per moved tail
-            const int total = n_run_s + n_tall_s + tails * per_tail;
+            const int total = n_run_s + n_tall_s + n_whole + n_cut * (cutting ? down_splits : 1);
             if (which == 0) { plan->n_gate_up = total; plan->n_run_up = n_run_s; }
-            else { plan->n_down = total; plan->n_run_down = n_run_s; plan->n_split_tails = down_splits > 1 ? tails : 0; }
+            else { plan->n_down = total; plan->n_run_down = n_run_s; plan->n_split_tails = n_cut; }
         }
         if (mine) {
             TileDesc d;
@@ -701,14 +728,15 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
                 d.row0 = row_begin + nfull * tm;
                 d.nrows = tail;
                 const int tbase = n_run_s + n_tall_s;
-                if (which == 1 && down_splits > 1) {
+                if (cutting && blocks <= split_max_blocks) {
                     // one entry per K piece; the pieces' partial sums are added up after the launch
+                    const int q = rank - n_whole;   // falling height: the whole ones rank first
                     for (int sp = 0; sp < down_splits; ++sp) {
-                        d.srow = -2 - (rank * down_splits + sp);
-                        descs[tbase + rank * down_splits + sp] = d;
+                        d.srow = -2 - (q * down_splits + sp);
+                        descs[tbase + n_whole + q * down_splits + sp] = d;
                     }
-                    split_tails[rank].row0 = d.row0;
-                    split_tails[rank].nrows = tail;
+                    split_tails[q].row0 = d.row0;
+                    split_tails[q].nrows = tail;
                 } else {
                     descs[tbase + rank] = d;
                 }
@@ -775,11 +803,12 @@ hipError_t ffn_gemm_init() {
 
 hipError_t launch_ffn_plan(const moe_shape& s, const int32_t* offsets, int tm_up, int tm_down, bool tails_last_up,
                            bool tails_last_down, bool small_tiles, int e_lo, int e_hi, bool shared_on,
-                           int down_tail_splits, int tall_up, int tall_down, SplitTail* split_tails, PlanHeader* plan,
-                           TileDesc* descs_up, TileDesc* descs_down, hipStream_t st) {
+                           int down_tail_splits, int split_max_blocks, int split_rule_tiles, int tall_up, int tall_down,
+                           SplitTail* split_tails, PlanHeader* plan, TileDesc* descs_up, TileDesc* descs_down, hipStream_t st) {
     hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(256), 0, st, offsets, s.T, (s.T + 15) & ~15, s.E, s.num_shared, tm_up, tm_down,
                        tails_last_up ? 1 : 0, tails_last_down ? 1 : 0, small_tiles ? 1 : 0, e_lo, e_hi, shared_on ? 1 : 0,
-                       tails_last_down ? down_tail_splits : 1, tall_up, tall_down, split_tails, plan, descs_up, descs_down);
+                       tails_last_down ? down_tail_splits : 1, split_max_blocks, split_rule_tiles, tall_up, tall_down, split_tails, plan, descs_up,
+                       descs_down);
     return hipGetLastError();
 }
 

@@ -30,6 +30,20 @@ def fuzz_seeds(default):
     return range(int(os.environ.get("MOE_FUZZ_SEEDS", default)))
 
 
+class forced_k_pieces:
+    """Option "down_tail_splits" = 2 for the duration: every eligible short tail of the down GEMM is cut
+    along K, also where the library would not choose to (it cuts by itself only in launches that
+    are all short tails, or many rounds long)."""
+    def __init__(self, moe, mode=2):
+        self.moe, self.mode = moe, mode
+
+    def __enter__(self):
+        self.moe.set_option("down_tail_splits", self.mode)
+
+    def __exit__(self, *exc):
+        self.moe.set_option("down_tail_splits", 1)
+
+
 def say(*a):
     print(*a, flush=True)
 
@@ -393,14 +407,17 @@ def test_layer_short_shared_tail_next_to_k_split_tails(moe, T, F, E, Ns):
     cfg = scaled_config("C4", T=T, H=256, F=F, E=E, top_k=min(4, E), num_shared=Ns)
     say("shared tail", cfg)
     gl = P.GpuLayer(moe, make_layer_inputs(cfg, device="cuda"))
-    out, out16 = gl.run_layer_both()
+    with forced_k_pieces(moe):
+        out, out16 = gl.run_layer_both()
     say(json.dumps(P.check_layer_against_oracle(gl, out, out16=out16)))
 
 
+@pytest.mark.parametrize("mode", [2, 1])
 @pytest.mark.parametrize("seed", fuzz_seeds(12))
-def test_layer_random_k_split_shapes(moe, seed):
+def test_layer_random_k_split_shapes(moe, seed, mode):
     """Seeded random shapes inside the K-split-tail regime (E <= 32, F a multiple of 128 from 512
-    up), with and without shared experts, every token against the oracle."""
+    up), with and without shared experts, every token against the oracle; with the pieces forced
+    (mode 2) and left to the library's own rule (mode 1)."""
     rng = np.random.default_rng(5000 + seed)
     E = int(rng.integers(1, 33))
     cfg = scaled_config(
@@ -408,9 +425,10 @@ def test_layer_random_k_split_shapes(moe, seed):
         T=int(rng.integers(1, 1200)), H=64 * int(rng.integers(1, 5)), F=128 * int(rng.integers(4, 13)),
         E=E, top_k=int(rng.integers(1, min(E, 6) + 1)), num_shared=int(rng.integers(1, 4)) if seed % 3 else 0,
         bias=["none", "normal", "logzipf_rank"][seed % 3])
-    say("random k-split", cfg)
+    say("random k-split", cfg, "mode", mode)
     gl = P.GpuLayer(moe, make_layer_inputs(cfg, device="cuda"))
-    out, out16 = gl.run_layer_both()
+    with forced_k_pieces(moe, mode):
+        out, out16 = gl.run_layer_both()
     say(json.dumps(P.check_layer_against_oracle(gl, out, out16=out16)))
 
 
@@ -437,6 +455,7 @@ def test_layer_fuzz_entry_points_and_options(moe, seed):
         bias=["none", "normal", "logzipf_rank"][seed % 3])
     say("fuzz", cfg)
     gl = P.GpuLayer(moe, make_layer_inputs(cfg, device="cuda"))
+    moe.set_option("down_tail_splits", 2 if seed % 4 == 0 else 1)   # a quarter of the cases with forced K pieces
     out, out16 = gl.run_layer_both()
     say(json.dumps(P.check_layer_against_oracle(gl, out, out16=out16)))
 
@@ -548,7 +567,7 @@ def test_accumulate_then_chunked_layer(moe):
     out_c = torch.empty((cfg.T, cfg.H), dtype=torch.float32, device="cuda")
     moe.set_option("out_fp32", 1)
     try:
-        for splits in (0, 1):
+        for splits in (0, 2):
             moe.set_option("down_tail_splits", splits)
             ref = torch.empty_like(out_c)
             moe.layer(gl.shape, staging, gl.wg, gl.bias, gl.w1p, gl.w3p, gl.w2p, ref, gl.ws, tables=gl.tables)

@@ -304,10 +304,12 @@ def test_grouped_ffn_every_tail_class(moe, F, num_shared, tall):
     idx_h = idx_h[np.random.default_rng(5).permutation(T)].reshape(T, 1)
     say("tail classes", cfg, "tall_tiles", tall)
     moe.set_option("tall_tiles", tall)
+    moe.set_option("down_tail_splits", 2)   # cut every eligible tail (the library's own rule would not, in a launch this short)
     try:
         y, ysh, perm, off, li = run_ffn_stage(moe, cfg, idx_h, wave_rows=1)
     finally:
         moe.set_option("tall_tiles", -1)
+        moe.set_option("down_tail_splits", 1)
     np.testing.assert_array_equal(np.diff(off), counts)
     u = torch_bf16_to_u16
     hw1 = [u(t) for t in li.w1]; hw3 = [u(t) for t in li.w3]; hw2 = [u(t) for t in li.w2]
